@@ -1,0 +1,104 @@
+/*
+ * bed -- batched symmetric eigendecomposition for AMD MI355X (gfx950).
+ *
+ * C ABI of libbed.so.  Every pointer marked "device" is GPU memory owned by
+ * the caller; the library allocates nothing and keeps no state between calls.
+ * All entry points are asynchronous: they enqueue one kernel on `stream`
+ * (a hipStream_t passed as void*; NULL = the default stream) and return.
+ * Argument errors are detected on the host, return a negative bed_status and
+ * enqueue nothing.  Entry points are re-entrant and thread-safe.
+ *
+ * Method (arXiv 2207.04228, Sec. 3): Householder tridiagonalisation
+ * A = P T P^T (Sec. 3.1), then QR iterations on T by Givens rotations with
+ * the two Wilkinson shifts taken from the trailing 2x2 block (Sec. 3.2.1,
+ * 3.2.2, App. A.1, A.3), per-matrix deflation of converged rows
+ * (Sec. 3.2.3, generalised from the last row to any negligible off-diagonal),
+ * and accumulation of all rotations into V = P Q_0 ... Q_k (closing equation
+ * of Sec. 3.2.1, Sec. 3.2.5).
+ */
+#ifndef BED_H
+#define BED_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BED_MAX_N 64
+#define BED_VERSION 100 /* major*10000 + minor*100 + patch */
+
+typedef enum {
+    BED_OK = 0,
+    BED_ERR_NULL = -1,   /* a required pointer is NULL                      */
+    BED_ERR_BATCH = -2,  /* batch < 0                                       */
+    BED_ERR_N = -3,      /* n < 1 or n > BED_MAX_N                          */
+    BED_ERR_ALIGN = -4,  /* a pointer is not 4-byte aligned                 */
+    BED_ERR_LAUNCH = -5, /* the HIP runtime refused the launch              */
+    BED_ERR_ALIAS = -6   /* an output buffer overlaps the input             */
+} bed_status;
+
+/*
+ * Eigendecomposition A_b = V_b diag(lambda_b) V_b^T of `batch` symmetric
+ * n x n matrices (the problem stated in Sec. 3.1 Eq. (1) and the closing
+ * equation of Sec. 3.2.1).
+ *
+ *   A      device, const, [batch][n][n] row-major fp32.  Only the LOWER
+ *          triangle (i >= j) is read; it is mirrored.  Not modified.
+ *   batch  >= 0; 0 is a no-op that returns BED_OK.
+ *   n      1 .. BED_MAX_N.
+ *   evals  device, [batch][n] fp32, ascending.
+ *   evecs  device, [batch][n][n] row-major fp32; evecs[b][i][j] is component i
+ *          of the eigenvector belonging to evals[b][j] (columns are
+ *          eigenvectors, orthonormal).  May be NULL: eigenvalues only, the
+ *          Householder accumulation and all rotations of V are skipped.
+ *   stream hipStream_t or NULL.
+ *
+ * Numerical non-convergence never aborts: the QR loop is capped (30 sweeps
+ * per row), a NaN/Inf input yields NaNs for that matrix only.  Use
+ * bed_syevd_info to observe it.
+ */
+int bed_syevd(const float* A, int batch, int n, float* evals, float* evecs,
+              void* stream);
+
+/*
+ * Same as bed_syevd, plus per-matrix diagnostics (either may be NULL):
+ *   info       device, [batch] int32: 0 = converged; k > 0 = k off-diagonal
+ *              entries of T were still not negligible when the sweep cap was
+ *              reached (or the input held NaN/Inf).
+ *   rotations  device, [batch] uint32: number of Givens rotations applied to
+ *              this matrix (the R of the flop model R*(6n+20); the paper
+ *              reports the related "reduction times" in App. C.4).
+ */
+int bed_syevd_info(const float* A, int batch, int n, float* evals, float* evecs,
+                   int* info, unsigned* rotations, void* stream);
+
+/*
+ * Stage hook 1 -- Householder tridiagonalisation only (Sec. 3.1, Eqs. (2)-(7)):
+ * A_b = P_b T_b P_b^T with T symmetric tridiagonal.
+ *   d  device, [batch][n]   diagonal of T
+ *   e  device, [batch][n]   e[b][k] = T[k+1][k] for k < n-1; e[b][n-1] = 0
+ *   P  device, [batch][n][n] row-major, the product of the n-2 reflectors
+ *      (first row and column are those of the identity).  May be NULL.
+ */
+int bed_tridiag(const float* A, int batch, int n, float* d, float* e, float* P,
+                void* stream);
+
+/*
+ * Stage hook 2 -- shifted QR iterations on a given symmetric tridiagonal
+ * matrix (Sec. 3.2): diag d, sub-diagonal e (same layout as bed_tridiag
+ * writes; e[b][n-1] is ignored).  evals ascending; evecs (may be NULL) are
+ * the eigenvectors of T as columns.
+ */
+int bed_tridiag_qr(const float* d, const float* e, int batch, int n,
+                   float* evals, float* evecs, int* info, unsigned* rotations,
+                   void* stream);
+
+/* Human-readable name of a bed_status value (static storage). */
+const char* bed_status_string(int status);
+
+/* BED_VERSION the library was built with. */
+int bed_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BED_H */

@@ -1,0 +1,17 @@
+"""bed -- batched symmetric eigendecomposition for MI355X (gfx950).
+
+Python binding over the C-ABI library ``libbed.so`` (see ``include/bed.h``).
+The library is loaded lazily on first use; importing this package never
+touches the GPU.
+"""
+from .binding import (  # noqa: F401
+    BedError,
+    bed_syevd,
+    bed_syevd_info,
+    bed_tridiag,
+    bed_tridiag_qr,
+    bed_version,
+    bed_status_string,
+    library_path,
+    load_library,
+)

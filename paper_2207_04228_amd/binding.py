@@ -1,0 +1,159 @@
+"""ctypes binding over libbed.so -- argument marshalling only.
+
+Every function takes torch CUDA tensors (used purely as device buffers),
+passes their raw pointers and the current HIP stream to the C ABI declared in
+``include/bed.h`` and raises ``BedError`` on a negative status.  There is no
+CPU fallback: if the library is missing, loading fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libbed.so")
+_lib = None
+
+BED_MAX_N = 64
+
+
+class BedError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: {bed_status_string(status)} ({status})")
+        self.status = status
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """dlopen libbed.so (built in-tree by ``paper_2207_04228_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} not found: build it with "
+                "`python -m paper_2207_04228_amd.build` (needs hipcc)")
+        lib = ctypes.CDLL(_LIB_PATH)
+        vp, ci = ctypes.c_void_p, ctypes.c_int
+        lib.bed_syevd.argtypes = [vp, ci, ci, vp, vp, vp]
+        lib.bed_syevd.restype = ci
+        lib.bed_syevd_info.argtypes = [vp, ci, ci, vp, vp, vp, vp, vp]
+        lib.bed_syevd_info.restype = ci
+        lib.bed_tridiag.argtypes = [vp, ci, ci, vp, vp, vp, vp]
+        lib.bed_tridiag.restype = ci
+        lib.bed_tridiag_qr.argtypes = [vp, vp, ci, ci, vp, vp, vp, vp, vp]
+        lib.bed_tridiag_qr.restype = ci
+        lib.bed_status_string.argtypes = [ci]
+        lib.bed_status_string.restype = ctypes.c_char_p
+        lib.bed_version.argtypes = []
+        lib.bed_version.restype = ci
+        _lib = lib
+    return _lib
+
+
+def bed_version() -> int:
+    return int(load_library().bed_version())
+
+
+def bed_status_string(status: int) -> str:
+    return load_library().bed_status_string(int(status)).decode()
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check_dev(t, name, dtype):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a CUDA tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+
+
+def bed_syevd(A, evals=None, evecs=None, *, want_vectors=True, stream=None):
+    """Eigendecomposition of A [batch, n, n] (float32, CUDA, symmetric; the
+    lower triangle is read).  Returns (evals [batch, n] ascending,
+    evecs [batch, n, n] with eigenvectors as columns, or None)."""
+    import torch
+    _check_dev(A, "A", torch.float32)
+    batch, n, n2 = A.shape
+    if n != n2:
+        raise ValueError("A must be [batch, n, n]")
+    if evals is None:
+        evals = torch.empty((batch, n), dtype=torch.float32, device=A.device)
+    if evecs is None and want_vectors:
+        evecs = torch.empty((batch, n, n), dtype=torch.float32, device=A.device)
+    _check_dev(evals, "evals", torch.float32)
+    if evecs is not None:
+        _check_dev(evecs, "evecs", torch.float32)
+    st = load_library().bed_syevd(_ptr(A), batch, n, _ptr(evals), _ptr(evecs), _stream(stream))
+    if st != 0:
+        raise BedError(st, "bed_syevd")
+    return evals, evecs
+
+
+def bed_syevd_info(A, evals=None, evecs=None, *, want_vectors=True, stream=None):
+    """bed_syevd plus (info int32 [batch], rotations int32-view of uint32 [batch])."""
+    import torch
+    _check_dev(A, "A", torch.float32)
+    batch, n, n2 = A.shape
+    if n != n2:
+        raise ValueError("A must be [batch, n, n]")
+    if evals is None:
+        evals = torch.empty((batch, n), dtype=torch.float32, device=A.device)
+    if evecs is None and want_vectors:
+        evecs = torch.empty((batch, n, n), dtype=torch.float32, device=A.device)
+    info = torch.empty((batch,), dtype=torch.int32, device=A.device)
+    rot = torch.empty((batch,), dtype=torch.int32, device=A.device)
+    st = load_library().bed_syevd_info(_ptr(A), batch, n, _ptr(evals), _ptr(evecs),
+                                       _ptr(info), _ptr(rot), _stream(stream))
+    if st != 0:
+        raise BedError(st, "bed_syevd_info")
+    return evals, evecs, info, rot
+
+
+def bed_tridiag(A, *, want_P=True, stream=None):
+    """Householder tridiagonalisation.  Returns (d [batch,n], e [batch,n], P or None)."""
+    import torch
+    _check_dev(A, "A", torch.float32)
+    batch, n, n2 = A.shape
+    if n != n2:
+        raise ValueError("A must be [batch, n, n]")
+    d = torch.empty((batch, n), dtype=torch.float32, device=A.device)
+    e = torch.empty((batch, n), dtype=torch.float32, device=A.device)
+    P = torch.empty((batch, n, n), dtype=torch.float32, device=A.device) if want_P else None
+    st = load_library().bed_tridiag(_ptr(A), batch, n, _ptr(d), _ptr(e), _ptr(P), _stream(stream))
+    if st != 0:
+        raise BedError(st, "bed_tridiag")
+    return d, e, P
+
+
+def bed_tridiag_qr(d, e, *, want_vectors=True, stream=None):
+    """Shifted QR iterations on tridiagonal (d, e).  Returns (evals, evecs, info, rotations)."""
+    import torch
+    _check_dev(d, "d", torch.float32)
+    _check_dev(e, "e", torch.float32)
+    batch, n = d.shape
+    if tuple(e.shape) != (batch, n):
+        raise ValueError("e must be [batch, n] (last entry of each row ignored)")
+    evals = torch.empty((batch, n), dtype=torch.float32, device=d.device)
+    evecs = torch.empty((batch, n, n), dtype=torch.float32, device=d.device) if want_vectors else None
+    info = torch.empty((batch,), dtype=torch.int32, device=d.device)
+    rot = torch.empty((batch,), dtype=torch.int32, device=d.device)
+    st = load_library().bed_tridiag_qr(_ptr(d), _ptr(e), batch, n, _ptr(evals), _ptr(evecs),
+                                       _ptr(info), _ptr(rot), _stream(stream))
+    if st != 0:
+        raise BedError(st, "bed_tridiag_qr")
+    return evals, evecs, info, rot
