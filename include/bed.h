@@ -63,7 +63,7 @@ int bed_syevd(const float* A, int batch, int n, float* evals, float* evecs,
  * Same as bed_syevd, plus per-matrix diagnostics (either may be NULL):
  *   info       device, [batch] int32: 0 = converged; k > 0 = k off-diagonal
  *              entries of T were still not negligible when the sweep cap was
- *              reached (or the input held NaN/Inf).
+ *              reached, or k eigenvalues came out non-finite (NaN/Inf input).
  *   rotations  device, [batch] uint32: number of Givens rotations applied to
  *              this matrix (the R of the flop model R*(6n+20); the paper
  *              reports the related "reduction times" in App. C.4).

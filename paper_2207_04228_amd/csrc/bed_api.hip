@@ -1,0 +1,117 @@
+// C ABI of libbed.so: argument validation and dispatch.  See include/bed.h.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "bed.h"
+#include "bed_kernel.h"
+
+namespace {
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) != 0; }
+
+bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+    if (!a || !b || na == 0 || nb == 0) return false;
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + nb && b0 < a0 + na;
+}
+
+int check_common(int batch, int n) {
+    if (batch < 0) return BED_ERR_BATCH;
+    if (n < 1 || n > BED_MAX_N) return BED_ERR_N;
+    return BED_OK;
+}
+
+int run(const bed::KernelArgs& args, int stage, bool want_v, void* stream) {
+    if (args.batch == 0) return BED_OK;
+    hipError_t err = bed::launch(args, stage, bed::kShiftDouble, want_v, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? BED_OK : BED_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int bed_syevd_info(const float* A, int batch, int n, float* evals, float* evecs, int* info,
+                   unsigned* rotations, void* stream) {
+    int st = check_common(batch, n);
+    if (st != BED_OK) return st;
+    if (!A || !evals) return BED_ERR_NULL;
+    if (misaligned(A) || misaligned(evals) || misaligned(evecs) || misaligned(info) || misaligned(rotations))
+        return BED_ERR_ALIGN;
+    const size_t mat = (size_t)batch * n * n * sizeof(float), vec = (size_t)batch * n * sizeof(float);
+    if (overlaps(A, mat, evals, vec) || overlaps(A, mat, evecs, mat) || overlaps(evals, vec, evecs, mat))
+        return BED_ERR_ALIAS;
+    bed::KernelArgs args{};
+    args.A = A;
+    args.evals = evals;
+    args.evecs = evecs;
+    args.info = info;
+    args.rotations = rotations;
+    args.batch = batch;
+    args.n = n;
+    return run(args, bed::kFull, evecs != nullptr, stream);
+}
+
+int bed_syevd(const float* A, int batch, int n, float* evals, float* evecs, void* stream) {
+    return bed_syevd_info(A, batch, n, evals, evecs, nullptr, nullptr, stream);
+}
+
+int bed_tridiag(const float* A, int batch, int n, float* d, float* e, float* P, void* stream) {
+    int st = check_common(batch, n);
+    if (st != BED_OK) return st;
+    if (!A || !d || !e) return BED_ERR_NULL;
+    if (misaligned(A) || misaligned(d) || misaligned(e) || misaligned(P)) return BED_ERR_ALIGN;
+    const size_t mat = (size_t)batch * n * n * sizeof(float), vec = (size_t)batch * n * sizeof(float);
+    if (overlaps(A, mat, d, vec) || overlaps(A, mat, e, vec) || overlaps(A, mat, P, mat) ||
+        overlaps(d, vec, e, vec) || overlaps(d, vec, P, mat) || overlaps(e, vec, P, mat))
+        return BED_ERR_ALIAS;
+    bed::KernelArgs args{};
+    args.A = A;
+    args.d_out = d;
+    args.e_out = e;
+    args.evecs = P;
+    args.batch = batch;
+    args.n = n;
+    return run(args, bed::kTridiagOnly, P != nullptr, stream);
+}
+
+int bed_tridiag_qr(const float* d, const float* e, int batch, int n, float* evals, float* evecs,
+                   int* info, unsigned* rotations, void* stream) {
+    int st = check_common(batch, n);
+    if (st != BED_OK) return st;
+    if (!d || !e || !evals) return BED_ERR_NULL;
+    if (misaligned(d) || misaligned(e) || misaligned(evals) || misaligned(evecs) || misaligned(info) ||
+        misaligned(rotations))
+        return BED_ERR_ALIGN;
+    const size_t mat = (size_t)batch * n * n * sizeof(float), vec = (size_t)batch * n * sizeof(float);
+    if (overlaps(d, vec, evals, vec) || overlaps(e, vec, evals, vec) || overlaps(d, vec, evecs, mat) ||
+        overlaps(e, vec, evecs, mat) || overlaps(evals, vec, evecs, mat))
+        return BED_ERR_ALIAS;
+    bed::KernelArgs args{};
+    args.d_in = d;
+    args.e_in = e;
+    args.evals = evals;
+    args.evecs = evecs;
+    args.info = info;
+    args.rotations = rotations;
+    args.batch = batch;
+    args.n = n;
+    return run(args, bed::kQrOnly, evecs != nullptr, stream);
+}
+
+const char* bed_status_string(int status) {
+    switch (status) {
+        case BED_OK: return "BED_OK";
+        case BED_ERR_NULL: return "BED_ERR_NULL: a required pointer is NULL";
+        case BED_ERR_BATCH: return "BED_ERR_BATCH: batch must be >= 0";
+        case BED_ERR_N: return "BED_ERR_N: n must be in 1..64";
+        case BED_ERR_ALIGN: return "BED_ERR_ALIGN: pointers must be 4-byte aligned";
+        case BED_ERR_LAUNCH: return "BED_ERR_LAUNCH: kernel launch failed";
+        case BED_ERR_ALIAS: return "BED_ERR_ALIAS: buffers overlap";
+        default: return "BED_ERR_UNKNOWN";
+    }
+}
+
+int bed_version(void) { return BED_VERSION; }
+
+}  // extern "C"

@@ -1,0 +1,19 @@
+// Size dispatch: picks the padded kernel size for n.
+#include "bed_kernel.h"
+
+namespace bed {
+
+hipError_t launch_wave_n8(const KernelArgs&, int, int, bool, hipStream_t);
+hipError_t launch_wave_n16(const KernelArgs&, int, int, bool, hipStream_t);
+hipError_t launch_wave_n32(const KernelArgs&, int, int, bool, hipStream_t);
+hipError_t launch_wave_n64(const KernelArgs&, int, int, bool, hipStream_t);
+
+hipError_t launch(const KernelArgs& args, int stage, int shift, bool want_v, hipStream_t stream) {
+    if (args.batch == 0) return hipSuccess;
+    if (args.n <= 8) return launch_wave_n8(args, stage, shift, want_v, stream);
+    if (args.n <= 16) return launch_wave_n16(args, stage, shift, want_v, stream);
+    if (args.n <= 32) return launch_wave_n32(args, stage, shift, want_v, stream);
+    return launch_wave_n64(args, stage, shift, want_v, stream);
+}
+
+}  // namespace bed

@@ -1,0 +1,66 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol that
+include/bed.h declares, and rejects bad arguments on the host without
+touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2207_04228_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.library_path()):
+        from paper_2207_04228_amd import build
+        build.build()
+    return binding.load_library()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "bed.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bed_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = _declared_symbols()
+    assert {"bed_syevd", "bed_syevd_info", "bed_tridiag", "bed_tridiag_qr",
+            "bed_status_string", "bed_version"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_version_and_status_strings(lib):
+    assert binding.bed_version() == 100
+    assert binding.bed_status_string(0) == "BED_OK"
+    for code in (-1, -2, -3, -4, -5, -6):
+        assert binding.bed_status_string(code).startswith("BED_ERR_")
+    assert "UNKNOWN" in binding.bed_status_string(-99)
+
+
+def test_argument_validation_is_host_side(lib):
+    p = lambda x: ctypes.c_void_p(x)
+    A, L, V = p(0x10000), p(0x20000), p(0x30000)
+    assert lib.bed_syevd(None, 1, 4, L, V, None) == -1          # NULL A
+    assert lib.bed_syevd(A, 1, 4, None, V, None) == -1          # NULL evals
+    assert lib.bed_syevd(A, -1, 4, L, V, None) == -2            # batch < 0
+    assert lib.bed_syevd(A, 1, 0, L, V, None) == -3             # n < 1
+    assert lib.bed_syevd(A, 1, 65, L, V, None) == -3            # n > 64
+    assert lib.bed_syevd(p(0x10002), 1, 4, L, V, None) == -4    # misaligned
+    assert lib.bed_syevd(A, 1, 4, L, p(0x10010), None) == -6    # evecs overlaps A
+    assert lib.bed_syevd(A, 0, 4, L, V, None) == 0              # batch 0: no-op
+    assert lib.bed_tridiag(A, 1, 4, None, L, V, None) == -1
+    assert lib.bed_tridiag(A, 0, 4, L, V, None, None) == 0
+    assert lib.bed_tridiag_qr(A, None, 1, 4, L, V, None, None, None) == -1
+    assert lib.bed_tridiag_qr(A, L, 0, 4, V, None, None, None, None) == 0
+    assert lib.bed_syevd_info(A, 1, 4, L, V, p(0x40001), None, None) == -4
+
+
+def test_binding_rejects_cpu_tensors():
+    import torch
+    with pytest.raises(TypeError):
+        binding.bed_syevd(torch.zeros(2, 4, 4))
