@@ -35,6 +35,7 @@ int bed_syevd_info(const float* A, int batch, int n, float* evals, float* evecs,
                    unsigned* rotations, void* stream) {
     int st = check_common(batch, n);
     if (st != BED_OK) return st;
+    if (batch == 0) return BED_OK;
     if (!A || !evals) return BED_ERR_NULL;
     if (misaligned(A) || misaligned(evals) || misaligned(evecs) || misaligned(info) || misaligned(rotations))
         return BED_ERR_ALIGN;
@@ -59,6 +60,7 @@ int bed_syevd(const float* A, int batch, int n, float* evals, float* evecs, void
 int bed_tridiag(const float* A, int batch, int n, float* d, float* e, float* P, void* stream) {
     int st = check_common(batch, n);
     if (st != BED_OK) return st;
+    if (batch == 0) return BED_OK;
     if (!A || !d || !e) return BED_ERR_NULL;
     if (misaligned(A) || misaligned(d) || misaligned(e) || misaligned(P)) return BED_ERR_ALIGN;
     const size_t mat = (size_t)batch * n * n * sizeof(float), vec = (size_t)batch * n * sizeof(float);
@@ -79,6 +81,7 @@ int bed_tridiag_qr(const float* d, const float* e, int batch, int n, float* eval
                    int* info, unsigned* rotations, void* stream) {
     int st = check_common(batch, n);
     if (st != BED_OK) return st;
+    if (batch == 0) return BED_OK;
     if (!d || !e || !evals) return BED_ERR_NULL;
     if (misaligned(d) || misaligned(e) || misaligned(evals) || misaligned(evecs) || misaligned(info) ||
         misaligned(rotations))

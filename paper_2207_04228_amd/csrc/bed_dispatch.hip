@@ -1,18 +1,25 @@
-// Size dispatch: picks the padded kernel size for n.
+// Size dispatch: picks the kernel whose register arrays fit n.
 #include "bed_kernel.h"
 
 namespace bed {
 
+hipError_t launch_wave_n4(const KernelArgs&, int, int, bool, hipStream_t);
 hipError_t launch_wave_n8(const KernelArgs&, int, int, bool, hipStream_t);
 hipError_t launch_wave_n16(const KernelArgs&, int, int, bool, hipStream_t);
+hipError_t launch_wave_n24(const KernelArgs&, int, int, bool, hipStream_t);
 hipError_t launch_wave_n32(const KernelArgs&, int, int, bool, hipStream_t);
+hipError_t launch_wave_n48(const KernelArgs&, int, int, bool, hipStream_t);
 hipError_t launch_wave_n64(const KernelArgs&, int, int, bool, hipStream_t);
 
 hipError_t launch(const KernelArgs& args, int stage, int shift, bool want_v, hipStream_t stream) {
     if (args.batch == 0) return hipSuccess;
-    if (args.n <= 8) return launch_wave_n8(args, stage, shift, want_v, stream);
-    if (args.n <= 16) return launch_wave_n16(args, stage, shift, want_v, stream);
-    if (args.n <= 32) return launch_wave_n32(args, stage, shift, want_v, stream);
+    const int n = args.n;
+    if (n <= 4) return launch_wave_n4(args, stage, shift, want_v, stream);
+    if (n <= 8) return launch_wave_n8(args, stage, shift, want_v, stream);
+    if (n <= 16) return launch_wave_n16(args, stage, shift, want_v, stream);
+    if (n <= 24) return launch_wave_n24(args, stage, shift, want_v, stream);
+    if (n <= 32) return launch_wave_n32(args, stage, shift, want_v, stream);
+    if (n <= 48) return launch_wave_n48(args, stage, shift, want_v, stream);
     return launch_wave_n64(args, stage, shift, want_v, stream);
 }
 

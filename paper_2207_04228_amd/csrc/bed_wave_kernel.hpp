@@ -1,18 +1,19 @@
-#ifndef BED_WAVE_KERNEL_HPP
-#define BED_WAVE_KERNEL_HPP
 // Batched symmetric eigensolver kernels for gfx950 (MI355X), wave64.
 //
-// One wavefront owns one matrix from load to store; lane r holds row r of the
-// working matrix and row r of the eigenvector accumulator in VGPRs.  The
-// whole path of arXiv 2207.04228 Sec. 3 runs inside one launch:
-//   Sec. 3.1   Householder tridiagonalisation (rank-2 update form, Eqs. (5)-(6)),
-//              accumulation of P (Eq. (8)) as rank-1 updates of V
+// One wavefront owns one matrix from load to store.  The whole path of
+// arXiv 2207.04228 Sec. 3 runs inside one launch:
+//   Sec. 3.1   Householder tridiagonalisation (rank-2 update form, Eqs. (5)-(6));
+//              lane r holds row r of the working matrix and row r of the
+//              accumulated reflector product P (Eq. (8)) in VGPRs
 //   Sec. 3.2   QR iterations by Givens rotations (App. A.1) with the two
 //              Wilkinson shifts of the trailing 2x2 block (Sec. 3.2.2, App. A.3),
 //              per-matrix deflation (Sec. 3.2.3), O(1) update of the
 //              tridiagonal per rotation (Sec. 3.2.4) and rotation of two
-//              columns of V per rotation (Sec. 3.2.5)
+//              columns of V per rotation (Sec. 3.2.5); the tridiagonal and V
+//              (column-major) live in LDS, lane r owns row r of V
 // followed by an ascending sort and a coalesced store.
+#ifndef BED_WAVE_KERNEL_HPP
+#define BED_WAVE_KERNEL_HPP
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -25,52 +26,59 @@ namespace {
 constexpr float kEps = 1.1920929e-7f;   // 2^-23: relative deflation tolerance
 constexpr float kTinyE = 1.0e-18f;      // absolute floor for |e| (matrix is pre-scaled to max|a| in [0.5,1))
 constexpr float kTinyH = 1.0e-37f;      // f^2+g^2 below this: rotation degenerates to the identity
+constexpr float kTinyAlpha = 1.0e-35f;  // |x|^2 below this: column already reduced, reflector skipped
 
 // ---- cross-lane helpers ---------------------------------------------------
 
-template <int CTRL>
-__device__ __forceinline__ float dpp(float x) {
-    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), CTRL, 0xF, 0xF, true));
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp0(float x) {
+    // lanes not selected by ROW_MASK (or reading out of range) receive 0
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xF, false));
 }
 
-constexpr int kQuadXor1 = 0xB1;      // quad_perm [1,0,3,2]
-constexpr int kQuadXor2 = 0x4E;      // quad_perm [2,3,0,1]
+constexpr int kQuadXor1 = 0xB1;       // quad_perm [1,0,3,2]
+constexpr int kQuadXor2 = 0x4E;       // quad_perm [2,3,0,1]
 constexpr int kRowHalfMirror = 0x141;
 constexpr int kRowMirror = 0x140;
-constexpr int kWaveShl1 = 0x130;     // lane i reads lane i+1
-
-// All-reduce (sum) over lanes [0, N) of the wave; every lane of that range
-// ends with the total.  Butterfly: quad xor 1, xor 2, then mirrors act as
-// xor 4 / xor 8 on quad-uniform values, then LDS-crossbar shuffles.
-template <int N>
-__device__ __forceinline__ float group_sum(float x) {
-    x += dpp<kQuadXor1>(x);
-    x += dpp<kQuadXor2>(x);
-    if (N >= 8) x += dpp<kRowHalfMirror>(x);
-    if (N >= 16) x += dpp<kRowMirror>(x);
-    if (N >= 32) x += __shfl_xor(x, 16, 64);
-    if (N >= 64) x += __shfl_xor(x, 32, 64);
-    return x;
-}
-
-template <int N>
-__device__ __forceinline__ float group_max(float x) {
-    x = fmaxf(x, dpp<kQuadXor1>(x));
-    x = fmaxf(x, dpp<kQuadXor2>(x));
-    if (N >= 8) x = fmaxf(x, dpp<kRowHalfMirror>(x));
-    if (N >= 16) x = fmaxf(x, dpp<kRowMirror>(x));
-    if (N >= 32) x = fmaxf(x, __shfl_xor(x, 16, 64));
-    if (N >= 64) x = fmaxf(x, __shfl_xor(x, 32, 64));
-    return x;
-}
-
-__device__ __forceinline__ float uniform(float x) {
-    return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(x)));
-}
+constexpr int kRowBcast15 = 0x142;    // lane 15 of each row -> every lane of the next row
+constexpr int kRowBcast31 = 0x143;    // lane 31 -> every lane of rows 2 and 3
 
 __device__ __forceinline__ float read_lane(float x, int lane_uniform) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), lane_uniform));
 }
+
+// Sum over lanes [0, W) of the wave (W = 8, 16, 32 or 64, lanes outside must
+// hold 0 or are ignored), returned as a wave-uniform value.  Quad butterflies,
+// then mirrors (which act as xor 4 / xor 8 on quad-uniform values), then row
+// broadcasts; no LDS traffic.
+template <int W>
+__device__ __forceinline__ float wave_sum(float x) {
+    x += dpp0<kQuadXor1>(x);
+    x += dpp0<kQuadXor2>(x);
+    x += dpp0<kRowHalfMirror>(x);
+    if (W >= 16) x += dpp0<kRowMirror>(x);
+    if (W <= 16) return read_lane(x, 0);
+    x += dpp0<kRowBcast15, 0xA>(x);
+    if (W == 32) return read_lane(x, 31);
+    x += dpp0<kRowBcast31, 0xC>(x);
+    return read_lane(x, 63);
+}
+
+// Same for max of non-negative values.
+template <int W>
+__device__ __forceinline__ float wave_max_nonneg(float x) {
+    x = fmaxf(x, dpp0<kQuadXor1>(x));
+    x = fmaxf(x, dpp0<kQuadXor2>(x));
+    x = fmaxf(x, dpp0<kRowHalfMirror>(x));
+    if (W >= 16) x = fmaxf(x, dpp0<kRowMirror>(x));
+    if (W <= 16) return read_lane(x, 0);
+    x = fmaxf(x, dpp0<kRowBcast15, 0xA>(x));
+    if (W == 32) return read_lane(x, 31);
+    x = fmaxf(x, dpp0<kRowBcast31, 0xC>(x));
+    return read_lane(x, 63);
+}
+
+constexpr int lanes_for(int n) { return n <= 8 ? 8 : (n <= 16 ? 16 : (n <= 32 ? 32 : 64)); }
 
 // Monotone map float -> uint32 (total order; NaNs land at the ends).
 __device__ __forceinline__ uint32_t sort_key(float x) {
@@ -78,89 +86,93 @@ __device__ __forceinline__ uint32_t sort_key(float x) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// exact power-of-two scale bringing amax into [0.5, 1); 1 for 0 / non-finite
+__device__ __forceinline__ void pow2_scale(float amax, float& scale, float& inv_scale) {
+    int ex = 0;
+    if (amax > 0.f && amax < __builtin_inff()) ex = __builtin_amdgcn_frexp_expf(amax);
+    ex = min(max(ex, -125), 126);
+    scale = ldexpf(1.0f, -ex);
+    inv_scale = ldexpf(1.0f, ex);
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------
-// N      padded dimension (8, 16, 32, 64); n <= N at run time
+// N      register-array size (4, 8, 16, 24, 32, 48, 64); n <= N at run time
 // WANT_V accumulate eigenvectors
 // STAGE  kFull, kTridiagOnly (stage hook 1), kQrOnly (stage hook 2)
 // SHIFT  kShiftDouble: both eigenvalues of the trailing 2x2 are taken once per
 //        outer iteration (Sec. 3.2.2); the second sweep uses the second one
-//        unless the first sweep already deflated the window.
+//        unless the first sweep already changed the active window.
 //        kShiftSingle: the eigenvalue closer to the last diagonal entry is
 //        recomputed before every sweep.
 // ---------------------------------------------------------------------------
 template <int N, bool WANT_V, int STAGE, int SHIFT>
 __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
-    constexpr int LD = N + 1;
-    __shared__ float smat[N * LD];
+    constexpr int W = lanes_for(N);
+    constexpr int LD = N + 1;             // odd stride: conflict-free rows and columns
+    // V, column-major: V[r][c] at sV[c * LD + r]; also the staging buffer for load and store.
+    __shared__ float sV[(N + 2) * LD];
+    // tridiagonal: sP[k] = (e[k-1], d[k]); e[k] couples rows k and k+1
+    __shared__ float2 sP[N + 4];
     __shared__ float svec[64];
 
     const int lane = threadIdx.x;
+    const int vl = lane < N ? lane : N - 1;   // row of V this lane works on (idle lanes shadow the last row)
     const int b = blockIdx.x;
     const int n = args.n;
 
-    float a[N];
-    float v[N];
-    float d[N];
-    float e[N];
-    float dl = 0.f, el = 0.f;  // lane-distributed mirrors: lane k holds d[k], e[k]
     float inv_scale = 1.f;
 
-#pragma unroll
-    for (int c = 0; c < N; ++c) {
-        v[c] = (c == lane) ? 1.f : 0.f;
-        d[c] = 0.f;
-        e[c] = 0.f;
-    }
-
     if (STAGE != kQrOnly) {
+        float a[N];
+        float v[N];
+#pragma unroll
+        for (int c = 0; c < N; ++c) v[c] = (c == lane) ? 1.f : 0.f;
+
         // ---- load: coalesced into LDS, then row `lane` (lower triangle mirrored)
         const float* __restrict__ Ab = args.A + (size_t)b * n * n;
         const float rcp_n = 1.0f / (float)n;
         for (int idx = lane; idx < n * n; idx += 64) {
             int i = (int)(((float)idx + 0.5f) * rcp_n);
             int j = idx - i * n;
-            smat[i * LD + j] = Ab[idx];
+            sV[i * LD + j] = Ab[idx];
         }
         __syncthreads();
         float amax = 0.f;
 #pragma unroll
         for (int c = 0; c < N; ++c) {
             float x = 0.f;
-            if (lane < n && c < n) x = (c <= lane) ? smat[lane * LD + c] : smat[c * LD + lane];
+            if (lane < n && c < n) x = (c <= lane) ? sV[lane * LD + c] : sV[c * LD + lane];
             a[c] = x;
             amax = fmaxf(amax, fabsf(x));   // fmaxf drops NaNs; they still reach the output through the arithmetic
         }
         __syncthreads();
-        amax = uniform(group_max<N>(amax));
-        // exact power-of-two pre-scaling: max|a| -> [0.5, 1)
-        int ex = 0;
-        if (amax > 0.f && amax < __builtin_inff()) ex = __builtin_amdgcn_frexp_expf(amax);
-        ex = min(max(ex, -125), 126);
-        const float scale = ldexpf(1.0f, -ex);
-        inv_scale = ldexpf(1.0f, ex);
+        float scale;
+        pow2_scale(wave_max_nonneg<W>(amax), scale, inv_scale);
 #pragma unroll
         for (int c = 0; c < N; ++c) a[c] *= scale;
 
         // ---- Householder tridiagonalisation, column J reduced at step J ----
+        // Branch-free: a step that has nothing to do (J >= n-2, or the column is
+        // already reduced) runs with u = 0 and beta = 0.
 #pragma unroll
         for (int J = 0; J < N; ++J) {
-            // d[J] is final once columns 0..J-1 are reduced
-            {
-                float dj = read_lane(a[J], J);
-                d[J] = dj;
-                if (lane == J) dl = dj;
-            }
-            if (J < N - 2 && J < n - 2) {
-                const float x = (lane > J) ? a[J] : 0.f;           // A[r][J], r > J
-                const float alpha = uniform(group_sum<N>(x * x));    // |x|^2
-                const float x0 = read_lane(a[J], J + 1);             // A[J+1][J]
-                if (alpha > 0.f) {
-                    const float nrm = sqrtf(alpha);
-                    const float sigma = (x0 < 0.f) ? -nrm : nrm;     // sign chosen to avoid cancellation
-                    const float ur = (lane == J + 1) ? (x0 + sigma) : ((lane > J + 1) ? x : 0.f);
-                    const float beta = 1.0f / (alpha + fabsf(x0) * nrm);  // 2 / |u|^2
+            const float dJ = read_lane(a[J], J);      // final once columns 0..J-1 are reduced
+            float eJ = 0.f;
+            if (J < N - 1) {
+                const float x0 = read_lane(a[J], J + 1);     // A[J+1][J]
+                eJ = x0;                                      // kept as is when no reflector is applied
+                if (J < N - 2) {
+                    const float x = (lane > J) ? a[J] : 0.f;  // A[r][J], r > J
+                    const float alpha = wave_sum<W>(x * x);   // |x|^2
+                    const bool active = (J < n - 2) && (alpha > kTinyAlpha);
+                    const float nrm = __builtin_amdgcn_sqrtf(alpha);
+                    const float sigma = (x0 < 0.f) ? -nrm : nrm;   // sign chosen to avoid cancellation
+                    float ur = (lane == J + 1) ? (x0 + sigma) : ((lane > J + 1) ? x : 0.f);
+                    ur = active ? ur : 0.f;
+                    const float beta = active ? __builtin_amdgcn_rcpf(fmaf(fabsf(x0), nrm, alpha)) : 0.f;  // 2/|u|^2
+                    eJ = active ? -sigma : x0;
                     svec[lane] = ur;
                     __syncthreads();
                     float u[N];
@@ -173,10 +185,10 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                         p = fmaf(a[c], u[c], p);
                         if (WANT_V) w = fmaf(v[c], u[c], w);
                     }
-                    p *= beta;                                        // p = 2 A u / |u|^2
+                    p *= beta;                                    // p = 2 A u / |u|^2
                     w *= beta;
-                    const float K = 0.5f * beta * uniform(group_sum<N>(ur * p));
-                    const float q = fmaf(-K, ur, p);                  // q = p - K u (symmetric rank-2 form)
+                    const float K = 0.5f * beta * wave_sum<W>(ur * p);
+                    const float q = fmaf(-K, ur, p);              // q = p - K u (symmetric rank-2 form)
                     svec[lane] = q;
                     __syncthreads();
 #pragma unroll
@@ -187,39 +199,37 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                         if (WANT_V) v[c] = fmaf(-w, u[c], v[c]);
                     }
                     __syncthreads();
-                    e[J] = -sigma;
-                } else {
-                    e[J] = 0.f;
                 }
-                if (lane == J) el = e[J];
-            } else if (J < N - 1 && J == n - 2) {
-                const float ej = read_lane(a[J], J + 1);
-                e[J] = ej;
-                if (lane == J) el = ej;
+            }
+            // sP[J+1].x = e[J], sP[J].y = d[J]
+            if (lane == 0) {
+                sP[J].y = dJ;
+                sP[J + 1].x = (J < n - 1) ? eJ : 0.f;
             }
         }
+        if (lane == 0) sP[0].x = 0.f;
+        if (WANT_V) {
+#pragma unroll
+            for (int c = 0; c < N; ++c) {
+                if (lane < N) sV[c * LD + lane] = v[c];
+            }
+        }
+        __syncthreads();
     } else {
         // ---- stage hook 2: tridiagonal given ----
         float dv = 0.f, ev = 0.f;
         if (lane < n) dv = args.d_in[(size_t)b * n + lane];
         if (lane < n - 1) ev = args.e_in[(size_t)b * n + lane];
-        float amax = uniform(group_max<N>(fmaxf(fabsf(dv), fabsf(ev))));
-        int ex = 0;
-        if (amax > 0.f && amax < __builtin_inff()) ex = __builtin_amdgcn_frexp_expf(amax);
-        ex = min(max(ex, -125), 126);
-        const float scale = ldexpf(1.0f, -ex);
-        inv_scale = ldexpf(1.0f, ex);
-        dl = dv * scale;
-        el = ev * scale;
-        svec[lane] = dl;
-        __syncthreads();
-#pragma unroll
-        for (int c = 0; c < N; ++c) d[c] = svec[c];
-        __syncthreads();
-        svec[lane] = el;
-        __syncthreads();
-#pragma unroll
-        for (int c = 0; c < N; ++c) e[c] = svec[c];
+        float scale;
+        pow2_scale(wave_max_nonneg<64>(fmaxf(fabsf(dv), fabsf(ev))), scale, inv_scale);
+        if (lane < N) {
+            sP[lane].y = dv * scale;
+            sP[lane + 1].x = ev * scale;
+        }
+        if (lane == 0) sP[0].x = 0.f;
+        if (WANT_V) {
+            for (int c = 0; c < N; ++c) sV[c * LD + vl] = (c == vl) ? 1.f : 0.f;
+        }
         __syncthreads();
     }
 
@@ -228,23 +238,39 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
 
     if (STAGE == kTridiagOnly) {
         if (lane < n) {
-            args.d_out[(size_t)b * n + lane] = dl * inv_scale;
-            args.e_out[(size_t)b * n + lane] = (lane < n - 1) ? el * inv_scale : 0.f;
+            args.d_out[(size_t)b * n + lane] = sP[lane].y * inv_scale;
+            args.e_out[(size_t)b * n + lane] = (lane < n - 1) ? sP[lane + 1].x * inv_scale : 0.f;
+        }
+        if (WANT_V) {
+            float* __restrict__ Vb = args.evecs + (size_t)b * n * n;
+            const float rcp_n = 1.0f / (float)n;
+            for (int idx = lane; idx < n * n; idx += 64) {
+                int i = (int)(((float)idx + 0.5f) * rcp_n);
+                int j = idx - i * n;
+                Vb[idx] = sV[j * LD + i];
+            }
         }
     } else {
-        // ---- shifted QR iterations on (d, e) ----
+        // ---- shifted QR iterations on the tridiagonal in sP ----
         const uint32_t cap = 30u * (uint32_t)n;
         uint32_t sweeps = 0;
         bool have_second = false;
         float mu_second = 0.f;
         int prev_lo = -1, prev_hi = -1;
+        bool live = lane < n - 1;      // e[lane] not yet deflated
         uint64_t nz = 0;
+        float dl = 0.f;
         while (true) {
-            // deflation test, one off-diagonal per lane
-            const float dnext = __shfl_down(dl, 1, 64);
-            const bool live = (lane < n - 1) && (el != 0.f) &&
-                              !(fabsf(el) <= fmaxf(kEps * (fabsf(dl) + fabsf(dnext)), kTinyE));
-            if (!live) el = 0.f;
+            // deflation test, one off-diagonal per lane: lane k looks at e[k], d[k], d[k+1]
+            float el = 0.f, dnext = 0.f;
+            if (lane < N) {
+                const float2 pk = sP[lane];
+                const float2 pk1 = sP[lane + 1];
+                dl = pk.y;
+                el = pk1.x;
+                dnext = pk1.y;
+            }
+            live = live && !(fabsf(el) <= fmaxf(kEps * (fabsf(dl) + fabsf(dnext)), kTinyE));
             nz = __ballot(live);
             if (nz == 0 || sweeps >= cap) break;
             const int hi = 64 - __builtin_clzll(nz);          // e[hi-1] is the last live entry
@@ -259,11 +285,11 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                 // eigenvalues of [[ta, tb], [tb, td]] (App. A.3), smaller-angle root first
                 const float ta = read_lane(dl, hi - 1);
                 const float tb = read_lane(el, hi - 1);
-                const float td = read_lane(dl, hi);
+                const float td = read_lane(dnext, hi - 1);
                 const float delta = 0.5f * (ta - td);
-                const float rt = sqrtf(fmaf(delta, delta, tb * tb));
+                const float rt = __builtin_amdgcn_sqrtf(fmaf(delta, delta, tb * tb));
                 const float den = delta + ((delta >= 0.f) ? rt : -rt);
-                const float t = (tb * tb) / den;
+                const float t = (tb * tb) * __builtin_amdgcn_rcpf(den);
                 mu = td - t;          // eigenvalue closer to the last diagonal entry
                 mu_second = ta + t;   // the other eigenvalue of the block
                 have_second = true;
@@ -271,49 +297,48 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                 prev_hi = hi;
             }
 
-            // one implicit QR sweep over the window [lo, hi]
-            float g = read_lane(dl, lo) - mu;
+            // one implicit QR sweep over the window [lo, hi]: rotations k = lo .. hi-1
+            float dk = read_lane(dl, lo);
+            float ek = read_lane(el, lo);
+            float dk1 = read_lane(dnext, lo);
+            float g = dk - mu;
             float s = 1.f, c = 1.f, p = 0.f;
-            const uint64_t act = ((1ull << hi) - 1ull) & ~((1ull << lo) - 1ull);  // bits lo..hi-1
-#pragma unroll
-            for (int k = 0; k < N; ++k) {
-                if (k < N - 1 && ((act >> k) & 1ull)) {
-                    const float ek = e[k];
-                    const float f = s * ek;
-                    const float bb = c * ek;
-                    const float h = fmaf(f, f, g * g);
-                    const bool ok = h > kTinyH;
-                    float rinv = __builtin_amdgcn_rsqf(h);
-                    rinv = ok ? rinv : 0.f;
-                    const float r = h * rinv;
-                    if (k > 0) {
-                        e[k - 1] = r;
-                        if (lane == k - 1) el = r;
-                    }
-                    s = f * rinv;
-                    c = ok ? g * rinv : 1.f;
-                    g = d[k] - p;
-                    const float r2 = fmaf(d[k + 1] - g, s, 2.f * c * bb);
-                    p = s * r2;
-                    const float dk = g + p;
-                    d[k] = dk;
-                    if (lane == k) dl = dk;
-                    g = fmaf(c, r2, -bb);
-                    if (WANT_V) {
-                        const float x = v[k], y = v[k + 1];
-                        v[k] = fmaf(c, x, s * y);
-                        v[k + 1] = fmaf(c, y, -s * x);
-                    }
-                } else if (k == hi) {
-                    const float dk = d[k] - p;
-                    d[k] = dk;
-                    if (lane == k) dl = dk;
-                    e[k - 1] = g;
-                    if (lane == k - 1) el = g;
-                }
+            float2 pn = sP[lo + 2];                 // (e[lo+1], d[lo+2])
+            float x = 0.f, ynext = 0.f;
+            if (WANT_V) {
+                x = sV[lo * LD + vl];
+                ynext = sV[(lo + 1) * LD + vl];
             }
-            // the first rotation wrote a value into the mirror of e[lo-1], which is outside the window
-            if (lo > 0 && lane == lo - 1) el = 0.f;
+            for (int k = lo; k < hi; ++k) {
+                float y = ynext;
+                if (WANT_V) ynext = sV[(k + 2) * LD + vl];       // column k+2 <= N+1 exists (padding)
+                const float2 pnn = sP[k + 3];                      // (e[k+2], d[k+3]); index <= N+2
+                const float f = s * ek;
+                const float bb = c * ek;
+                const float h = fmaf(f, f, g * g);
+                const bool ok = h > kTinyH;
+                float rinv = __builtin_amdgcn_rsqf(h);
+                rinv = ok ? rinv : 0.f;
+                const float r = h * rinv;
+                s = f * rinv;
+                c = ok ? g * rinv : 1.f;
+                g = dk - p;
+                const float r2 = fmaf(dk1 - g, s, 2.f * c * bb);
+                p = s * r2;
+                sP[k] = make_float2(r, g + p);                     // e[k-1] = r, d[k] final
+                g = fmaf(c, r2, -bb);
+                if (WANT_V) {
+                    sV[k * LD + vl] = fmaf(c, x, s * y);
+                    x = fmaf(c, y, -s * x);
+                }
+                ek = pn.x;
+                dk = dk1;
+                dk1 = pn.y;
+                pn = pnn;
+            }
+            if (WANT_V) sV[hi * LD + vl] = x;
+            sP[hi] = make_float2(g, dk - p);                       // e[hi-1] = g, d[hi] -= p
+            __syncthreads();
             rotations += (uint32_t)(hi - lo);
             ++sweeps;
         }
@@ -324,46 +349,28 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
             info = max(info, (int)__builtin_popcountll(bad));
         }
 
-        // ---- ascending order ----
+        // ---- ascending order: rank of d[lane] among d[0..n) ----
         const uint32_t mykey = sort_key(dl);
         int rank = 0;
-#pragma unroll
-        for (int j = 0; j < N; ++j) {
-            if (j < n) {
-                const uint32_t kj = sort_key(d[j]);
-                rank += (kj < mykey || (kj == mykey && j < lane)) ? 1 : 0;
-            }
+        for (int j = 0; j < n; ++j) {
+            const uint32_t kj = sort_key(sP[j].y);
+            rank += (kj < mykey || (kj == mykey && j < lane)) ? 1 : 0;
         }
         if (lane < n) args.evals[(size_t)b * n + rank] = dl * inv_scale;
         if (WANT_V) {
-            int* srank = reinterpret_cast<int*>(svec);
-            srank[lane] = rank;
+            int* sinv = reinterpret_cast<int*>(svec);
+            if (lane < n) sinv[rank] = lane;       // output column `rank` comes from column `lane`
             __syncthreads();
-#pragma unroll
-            for (int c = 0; c < N; ++c) {
-                if (c < n && lane < n) smat[lane * LD + srank[c]] = v[c];
+            float* __restrict__ Vb = args.evecs + (size_t)b * n * n;
+            const float rcp_n = 1.0f / (float)n;
+            for (int idx = lane; idx < n * n; idx += 64) {
+                int i = (int)(((float)idx + 0.5f) * rcp_n);
+                int j = idx - i * n;
+                Vb[idx] = sV[sinv[j] * LD + i];
             }
-            __syncthreads();
         }
     }
 
-    if (STAGE == kTridiagOnly && WANT_V) {
-        __syncthreads();
-#pragma unroll
-        for (int c = 0; c < N; ++c) {
-            if (c < n && lane < n) smat[lane * LD + c] = v[c];
-        }
-        __syncthreads();
-    }
-    if (WANT_V) {
-        float* __restrict__ Vb = args.evecs + (size_t)b * n * n;
-        const float rcp_n = 1.0f / (float)n;
-        for (int idx = lane; idx < n * n; idx += 64) {
-            int i = (int)(((float)idx + 0.5f) * rcp_n);
-            int j = idx - i * n;
-            Vb[idx] = smat[i * LD + j];
-        }
-    }
     if (lane == 0) {
         if (args.info) args.info[b] = info;
         if (args.rotations) args.rotations[b] = rotations;
@@ -371,7 +378,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
 }
 
 // ---------------------------------------------------------------------------
-// host-side dispatch for one padded size
+// host-side dispatch for one register-array size
 // ---------------------------------------------------------------------------
 template <int N, bool WANT_V, int STAGE, int SHIFT>
 static hipError_t launch_one(const KernelArgs& args, hipStream_t stream) {

@@ -1,0 +1,8 @@
+// Instantiation of the one-wave-per-matrix kernels for register-array size 48.
+#include "bed_wave_kernel.hpp"
+
+namespace bed {
+hipError_t launch_wave_n48(const KernelArgs& args, int stage, int shift, bool want_v, hipStream_t stream) {
+    return launch_n<48>(args, stage, shift, want_v, stream);
+}
+}  // namespace bed
