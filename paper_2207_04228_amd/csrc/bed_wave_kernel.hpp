@@ -95,6 +95,116 @@ __device__ __forceinline__ void pow2_scale(float amax, float& scale, float& inv_
     inv_scale = ldexpf(1.0f, ex);
 }
 
+
+// ---- one sweep's running state (all values are wave-uniform except x) ------
+// Implicit shifted QR step written as a chain of Givens rotations (App. A.1):
+// rotation k acts on rows/columns (k, k+1), consumes e[k], d[k+1] and column
+// k+1 of V, and emits the final e[k-1], d[k] and column k of V.
+struct Chain {
+    float g, s, c, p;   // bulge-chase carries
+    float dk;           // d[k] as left by the previous rotation
+    float x;            // V[row][k], this lane's entry of the column being carried
+};
+
+template <bool WANT_V>
+__device__ __forceinline__ void chain_start(Chain& S, float d_lo, float mu, float v_lo) {
+    S.g = d_lo - mu;
+    S.s = 1.f;
+    S.c = 1.f;
+    S.p = 0.f;
+    S.dk = d_lo;
+    S.x = v_lo;
+}
+
+template <bool WANT_V>
+__device__ __forceinline__ void chain_rotate(Chain& S, float ek, float dk1, float y,
+                                             float& e_out, float& d_out, float& v_out) {
+    const float f = S.s * ek;
+    const float bb = S.c * ek;
+    const float h = fmaf(f, f, S.g * S.g);
+    const bool ok = h > kTinyH;
+    float rinv = __builtin_amdgcn_rsqf(h);
+    rinv = ok ? rinv : 0.f;
+    e_out = h * rinv;                        // e[k-1] = hypot(f, g)
+    S.s = f * rinv;
+    S.c = ok ? S.g * rinv : 1.f;
+    const float gg = S.dk - S.p;
+    const float r2 = fmaf(dk1 - gg, S.s, 2.f * S.c * bb);
+    S.p = S.s * r2;
+    d_out = gg + S.p;                        // d[k] final
+    S.g = fmaf(S.c, r2, -bb);
+    if (WANT_V) {
+        v_out = fmaf(S.c, S.x, S.s * y);     // column k final
+        S.x = fmaf(S.c, y, -S.s * S.x);      // column k+1, carried
+    }
+    S.dk = dk1;
+}
+
+// Two independent rotations (one per sweep) written statement by statement in
+// alternation, so that the in-order instruction stream always has an
+// independent instruction to issue behind a dependent one.
+template <bool WANT_V>
+__device__ __forceinline__ void chain_rotate2(Chain& A, float ekA, float dk1A, float yA,
+                                              float& eA, float& dA, float& vA,
+                                              Chain& B, float ekB, float dk1B, float yB,
+                                              float& eB, float& dB, float& vB) {
+    const float fA = A.s * ekA;
+    const float fB = B.s * ekB;
+    const float ggA = A.g * A.g;
+    const float ggB = B.g * B.g;
+    const float hA = fmaf(fA, fA, ggA);
+    const float hB = fmaf(fB, fB, ggB);
+    const float bA = A.c * ekA;
+    const float bB = B.c * ekB;
+    float riA = __builtin_amdgcn_rsqf(hA);
+    float riB = __builtin_amdgcn_rsqf(hB);
+    const bool okA = hA > kTinyH;
+    const bool okB = hB > kTinyH;
+    const float gA = A.dk - A.p;
+    const float gB = B.dk - B.p;
+    const float cA0 = A.g * riA;
+    const float cB0 = B.g * riB;
+    riA = okA ? riA : 0.f;
+    riB = okB ? riB : 0.f;
+    A.c = okA ? cA0 : 1.f;
+    B.c = okB ? cB0 : 1.f;
+    A.s = fA * riA;
+    B.s = fB * riB;
+    const float tA = dk1A - gA;
+    const float tB = dk1B - gB;
+    const float cbA = 2.f * A.c * bA;
+    const float cbB = 2.f * B.c * bB;
+    const float r2A = fmaf(tA, A.s, cbA);
+    const float r2B = fmaf(tB, B.s, cbB);
+    eA = hA * riA;
+    eB = hB * riB;
+    A.p = A.s * r2A;
+    B.p = B.s * r2B;
+    A.g = fmaf(A.c, r2A, -bA);
+    B.g = fmaf(B.c, r2B, -bB);
+    dA = gA + A.p;
+    dB = gB + B.p;
+    if (WANT_V) {
+        const float syA = A.s * yA;
+        const float syB = B.s * yB;
+        const float sxA = A.s * A.x;
+        const float sxB = B.s * B.x;
+        vA = fmaf(A.c, A.x, syA);
+        vB = fmaf(B.c, B.x, syB);
+        A.x = fmaf(A.c, yA, -sxA);
+        B.x = fmaf(B.c, yB, -sxB);
+    }
+    A.dk = dk1A;
+    B.dk = dk1B;
+}
+
+// end of a sweep at row hi: e[hi-1] = g, d[hi] -= p, column hi = carried column
+__device__ __forceinline__ void chain_finish(const Chain& S, float& e_out, float& d_out, float& v_out) {
+    e_out = S.g;
+    d_out = S.dk - S.p;
+    v_out = S.x;
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------
@@ -110,7 +220,9 @@ __device__ __forceinline__ void pow2_scale(float amax, float& scale, float& inv_
 template <int N, bool WANT_V, int STAGE, int SHIFT>
 __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
     constexpr int W = lanes_for(N);
-    constexpr int LD = N + 1;             // odd stride: conflict-free rows and columns
+    // Column stride 65: odd (conflict-free rows and columns) and wide enough that all 64
+    // lanes own a row slot, so no V access needs a lane predicate (rows >= n are idle lanes).
+    constexpr int LD = 65;
     // V, column-major: V[r][c] at sV[c * LD + r]; also the staging buffer for load and store.
     __shared__ float sV[(N + 2) * LD];
     // tridiagonal: sP[k] = (e[k-1], d[k]); e[k] couples rows k and k+1
@@ -118,7 +230,6 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
     __shared__ float svec[64];
 
     const int lane = threadIdx.x;
-    const int vl = lane < N ? lane : N - 1;   // row of V this lane works on (idle lanes shadow the last row)
     const int b = blockIdx.x;
     const int n = args.n;
 
@@ -210,9 +321,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         if (lane == 0) sP[0].x = 0.f;
         if (WANT_V) {
 #pragma unroll
-            for (int c = 0; c < N; ++c) {
-                if (lane < N) sV[c * LD + lane] = v[c];
-            }
+            for (int c = 0; c < N; ++c) sV[c * LD + lane] = v[c];
         }
         __syncthreads();
     } else {
@@ -228,7 +337,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         }
         if (lane == 0) sP[0].x = 0.f;
         if (WANT_V) {
-            for (int c = 0; c < N; ++c) sV[c * LD + vl] = (c == vl) ? 1.f : 0.f;
+            for (int c = 0; c < N; ++c) sV[c * LD + lane] = (c == lane) ? 1.f : 0.f;
         }
         __syncthreads();
     }
@@ -254,9 +363,6 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         // ---- shifted QR iterations on the tridiagonal in sP ----
         const uint32_t cap = 30u * (uint32_t)n;
         uint32_t sweeps = 0;
-        bool have_second = false;
-        float mu_second = 0.f;
-        int prev_lo = -1, prev_hi = -1;
         bool live = lane < n - 1;      // e[lane] not yet deflated
         uint64_t nz = 0;
         float dl = 0.f;
@@ -277,70 +383,104 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
             const uint64_t below = ~nz & ((1ull << (hi - 1)) - 1ull);
             const int lo = below ? 64 - __builtin_clzll(below) : 0;
 
-            float mu;
-            if (SHIFT == kShiftDouble && have_second && lo == prev_lo && hi == prev_hi) {
-                mu = mu_second;
-                have_second = false;
-            } else {
-                // eigenvalues of [[ta, tb], [tb, td]] (App. A.3), smaller-angle root first
-                const float ta = read_lane(dl, hi - 1);
-                const float tb = read_lane(el, hi - 1);
-                const float td = read_lane(dnext, hi - 1);
-                const float delta = 0.5f * (ta - td);
-                const float rt = __builtin_amdgcn_sqrtf(fmaf(delta, delta, tb * tb));
-                const float den = delta + ((delta >= 0.f) ? rt : -rt);
-                const float t = (tb * tb) * __builtin_amdgcn_rcpf(den);
-                mu = td - t;          // eigenvalue closer to the last diagonal entry
-                mu_second = ta + t;   // the other eigenvalue of the block
-                have_second = true;
-                prev_lo = lo;
-                prev_hi = hi;
-            }
+            // eigenvalues of the trailing block [[ta, tb], [tb, td]] (App. A.3), smaller-angle root first
+            const float ta = read_lane(dl, hi - 1);
+            const float tb = read_lane(el, hi - 1);
+            const float td = read_lane(dnext, hi - 1);
+            const float delta = 0.5f * (ta - td);
+            const float rt = __builtin_amdgcn_sqrtf(fmaf(delta, delta, tb * tb));
+            const float den = delta + ((delta >= 0.f) ? rt : -rt);
+            const float tt = (tb * tb) * __builtin_amdgcn_rcpf(den);
+            const float mu1 = td - tt;          // eigenvalue closer to the last diagonal entry
+            const float mu2 = ta + tt;          // the other eigenvalue of the block
 
-            // one implicit QR sweep over the window [lo, hi]: rotations k = lo .. hi-1
-            float dk = read_lane(dl, lo);
-            float ek = read_lane(el, lo);
-            float dk1 = read_lane(dnext, lo);
-            float g = dk - mu;
-            float s = 1.f, c = 1.f, p = 0.f;
+            const float d_lo = read_lane(dl, lo);
+            float ekA = read_lane(el, lo);
+            float dk1A = read_lane(dnext, lo);
             float2 pn = sP[lo + 2];                 // (e[lo+1], d[lo+2])
-            float x = 0.f, ynext = 0.f;
-            if (WANT_V) {
-                x = sV[lo * LD + vl];
-                ynext = sV[(lo + 1) * LD + vl];
-            }
-            for (int k = lo; k < hi; ++k) {
-                float y = ynext;
-                if (WANT_V) ynext = sV[(k + 2) * LD + vl];       // column k+2 <= N+1 exists (padding)
-                const float2 pnn = sP[k + 3];                      // (e[k+2], d[k+3]); index <= N+2
-                const float f = s * ek;
-                const float bb = c * ek;
-                const float h = fmaf(f, f, g * g);
-                const bool ok = h > kTinyH;
-                float rinv = __builtin_amdgcn_rsqf(h);
-                rinv = ok ? rinv : 0.f;
-                const float r = h * rinv;
-                s = f * rinv;
-                c = ok ? g * rinv : 1.f;
-                g = dk - p;
-                const float r2 = fmaf(dk1 - g, s, 2.f * c * bb);
-                p = s * r2;
-                sP[k] = make_float2(r, g + p);                     // e[k-1] = r, d[k] final
-                g = fmaf(c, r2, -bb);
-                if (WANT_V) {
-                    sV[k * LD + vl] = fmaf(c, x, s * y);
-                    x = fmaf(c, y, -s * x);
+            float ynext = 0.f;
+            Chain A;
+            chain_start<WANT_V>(A, d_lo, mu1, WANT_V ? sV[lo * LD + lane] : 0.f);
+            if (WANT_V) ynext = sV[(lo + 1) * LD + lane];
+
+            if (SHIFT == kShiftSingle) {
+                // one sweep over the window [lo, hi]: rotations k = lo .. hi-1
+                for (int k = lo; k < hi; ++k) {
+                    const float y = ynext;
+                    if (WANT_V) ynext = sV[(k + 2) * LD + lane];   // column k+2 <= N+1 exists (padding)
+                    const float2 pnn = sP[k + 3];                  // (e[k+2], d[k+3]); index <= N+2
+                    float eo, dq, vo = 0.f;
+                    chain_rotate<WANT_V>(A, ekA, dk1A, y, eo, dq, vo);
+                    sP[k] = make_float2(eo, dq);
+                    if (WANT_V) sV[k * LD + lane] = vo;
+                    ekA = pn.x;
+                    dk1A = pn.y;
+                    pn = pnn;
                 }
-                ek = pn.x;
-                dk = dk1;
-                dk1 = pn.y;
-                pn = pnn;
+                float eo, dq, vo;
+                chain_finish(A, eo, dq, vo);
+                sP[hi] = make_float2(eo, dq);
+                if (WANT_V) sV[hi * LD + lane] = vo;
+                rotations += (uint32_t)(hi - lo);
+                sweeps += 1;
+            } else {
+                // Two sweeps (shift mu1, then mu2) over the same window, software-pipelined:
+                // sweep B runs two rotations behind sweep A and takes A's results straight
+                // from registers, so the two dependency chains interleave in one
+                // instruction stream.  At iteration t: B handles row t-2 with A's outputs of
+                // iteration t-1, then A handles row t.
+                Chain B;
+                float pE, pD, pV = 0.f;     // A's outputs of the previous iteration
+                auto stepA = [&](int t) {
+                    if (t < hi) {
+                        const float y = ynext;
+                        if (WANT_V) ynext = sV[(t + 2) * LD + lane];
+                        const float2 pnn = sP[t + 3];
+                        chain_rotate<WANT_V>(A, ekA, dk1A, y, pE, pD, pV);
+                        ekA = pn.x;
+                        dk1A = pn.y;
+                        pn = pnn;
+                    } else {
+                        chain_finish(A, pE, pD, pV);
+                    }
+                };
+                auto stepB = [&](int j) {
+                    float eo, dq, vo = 0.f;
+                    if (j < hi) chain_rotate<WANT_V>(B, pE, pD, pV, eo, dq, vo);
+                    else chain_finish(B, eo, dq, vo);
+                    sP[j] = make_float2(eo, dq);
+                    if (WANT_V) sV[j * LD + lane] = vo;
+                };
+                stepA(lo);
+                chain_start<WANT_V>(B, pD, mu2, pV);      // d'[lo], column lo after sweep A
+                stepA(lo + 1);
+                int t = lo + 2;
+#pragma unroll 2
+                for (; t < hi; ++t) {
+                    // steady state: both sweeps rotate; one basic block, two independent chains
+                    float eo, dq, vo = 0.f;
+                    const float y = ynext;
+                    if (WANT_V) ynext = sV[(t + 2) * LD + lane];
+                    const float2 pnn = sP[t + 3];
+                    float nE, nD, nV = 0.f;
+                    chain_rotate2<WANT_V>(A, ekA, dk1A, y, nE, nD, nV, B, pE, pD, pV, eo, dq, vo);
+                    sP[t - 2] = make_float2(eo, dq);
+                    if (WANT_V) sV[(t - 2) * LD + lane] = vo;
+                    pE = nE;
+                    pD = nD;
+                    pV = nV;
+                    ekA = pn.x;
+                    dk1A = pn.y;
+                    pn = pnn;
+                }
+                for (; t - 2 <= hi; ++t) {
+                    stepB(t - 2);
+                    if (t == hi) stepA(t);
+                }
+                rotations += 2u * (uint32_t)(hi - lo);
+                sweeps += 2;
             }
-            if (WANT_V) sV[hi * LD + vl] = x;
-            sP[hi] = make_float2(g, dk - p);                       // e[hi-1] = g, d[hi] -= p
             __syncthreads();
-            rotations += (uint32_t)(hi - lo);
-            ++sweeps;
         }
         info = __builtin_popcountll(nz);
         {
