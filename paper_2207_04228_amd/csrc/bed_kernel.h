@@ -22,6 +22,9 @@ struct KernelArgs {
     uint32_t* rotations; // [batch] or nullptr
     int batch;
     int n;
+#ifdef BED_PROFILE
+    long long* prof;     // [batch][8] development-only phase timers
+#endif
 };
 
 // Enqueue one launch; returns hipGetLastError() of the launch.

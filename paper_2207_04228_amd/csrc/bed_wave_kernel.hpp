@@ -19,13 +19,24 @@
 
 #include "bed_kernel.h"
 
+#ifdef BED_PROFILE
+// Development-only phase timers (cycle counter deltas accumulated per probe id).
+#define BED_PROBE_INIT() long long prof_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}; long long prof_last = clock64(); int prof_id = 7
+#define BED_PROBE(i) do { long long now_ = clock64(); prof_acc[prof_id] += now_ - prof_last; prof_last = now_; prof_id = (i); } while (0)
+#define BED_PROBE_DUMP() do { BED_PROBE(7); if (lane == 0 && args.prof) for (int q_ = 0; q_ < 8; ++q_) args.prof[(size_t)b * 8 + q_] = prof_acc[q_]; } while (0)
+#else
+#define BED_PROBE_INIT() do {} while (0)
+#define BED_PROBE(i) do {} while (0)
+#define BED_PROBE_DUMP() do {} while (0)
+#endif
+
 namespace bed {
 
 namespace {
 
 constexpr float kEps = 1.1920929e-7f;   // 2^-23: relative deflation tolerance
 constexpr float kTinyE = 1.0e-18f;      // absolute floor for |e| (matrix is pre-scaled to max|a| in [0.5,1))
-constexpr float kTinyH = 1.0e-37f;      // f^2+g^2 below this: rotation degenerates to the identity
+constexpr float kTinyG = 1.0e-18f;      // floor for |g| in a rotation (keeps f^2+g^2 a normal number)
 constexpr float kTinyAlpha = 1.0e-35f;  // |x|^2 below this: column already reduced, reflector skipped
 
 // ---- cross-lane helpers ---------------------------------------------------
@@ -42,6 +53,12 @@ constexpr int kRowHalfMirror = 0x141;
 constexpr int kRowMirror = 0x140;
 constexpr int kRowBcast15 = 0x142;    // lane 15 of each row -> every lane of the next row
 constexpr int kRowBcast31 = 0x143;    // lane 31 -> every lane of rows 2 and 3
+
+// A workgroup is one wavefront, and a wavefront's LDS operations complete in
+// program order, so data written to LDS by one lane is visible to a later read
+// by another lane without a hardware barrier.  This only stops the compiler
+// from moving memory operations across the point.
+__device__ __forceinline__ void wave_sync() { __builtin_amdgcn_wave_barrier(); }
 
 __device__ __forceinline__ float read_lane(float x, int lane_uniform) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), lane_uniform));
@@ -116,23 +133,30 @@ __device__ __forceinline__ void chain_start(Chain& S, float d_lo, float mu, floa
     S.x = v_lo;
 }
 
+// |g| is kept away from zero (by 1e-18 of the pre-scaled matrix, far below
+// rounding) so that f^2 + g^2 is always a normal number: the rotation stays
+// exactly normalised and no compare/select sits on the dependency chain.
+__device__ __forceinline__ float guard_g(float g) {
+    const float mag = __builtin_amdgcn_fmed3f(fabsf(g), kTinyG, __builtin_inff());   // max(|g|, floor) in one instruction
+    return __uint_as_float((__float_as_uint(g) & 0x80000000u) | __float_as_uint(mag));
+}
+
 template <bool WANT_V>
 __device__ __forceinline__ void chain_rotate(Chain& S, float ek, float dk1, float y,
                                              float& e_out, float& d_out, float& v_out) {
+    const float g = guard_g(S.g);
     const float f = S.s * ek;
     const float bb = S.c * ek;
-    const float h = fmaf(f, f, S.g * S.g);
-    const bool ok = h > kTinyH;
-    float rinv = __builtin_amdgcn_rsqf(h);
-    rinv = ok ? rinv : 0.f;
-    e_out = h * rinv;                        // e[k-1] = hypot(f, g)
-    S.s = f * rinv;
-    S.c = ok ? S.g * rinv : 1.f;
+    const float h = fmaf(f, f, g * g);
+    const float rinv = __builtin_amdgcn_rsqf(h);
     const float gg = S.dk - S.p;
+    S.c = g * rinv;
+    S.s = f * rinv;
+    e_out = h * rinv;                        // e[k-1] = hypot(f, g)
     const float r2 = fmaf(dk1 - gg, S.s, 2.f * S.c * bb);
     S.p = S.s * r2;
-    d_out = gg + S.p;                        // d[k] final
     S.g = fmaf(S.c, r2, -bb);
+    d_out = gg + S.p;                        // d[k] final
     if (WANT_V) {
         v_out = fmaf(S.c, S.x, S.s * y);     // column k final
         S.x = fmaf(S.c, y, -S.s * S.x);      // column k+1, carried
@@ -148,30 +172,26 @@ __device__ __forceinline__ void chain_rotate2(Chain& A, float ekA, float dk1A, f
                                               float& eA, float& dA, float& vA,
                                               Chain& B, float ekB, float dk1B, float yB,
                                               float& eB, float& dB, float& vB) {
+    const float g0A = guard_g(A.g);
+    const float g0B = guard_g(B.g);
     const float fA = A.s * ekA;
     const float fB = B.s * ekB;
-    const float ggA = A.g * A.g;
-    const float ggB = B.g * B.g;
-    const float hA = fmaf(fA, fA, ggA);
-    const float hB = fmaf(fB, fB, ggB);
+    const float ggA = g0A * g0A;
+    const float ggB = g0B * g0B;
     const float bA = A.c * ekA;
     const float bB = B.c * ekB;
-    float riA = __builtin_amdgcn_rsqf(hA);
-    float riB = __builtin_amdgcn_rsqf(hB);
-    const bool okA = hA > kTinyH;
-    const bool okB = hB > kTinyH;
+    const float hA = fmaf(fA, fA, ggA);
+    const float hB = fmaf(fB, fB, ggB);
     const float gA = A.dk - A.p;
     const float gB = B.dk - B.p;
-    const float cA0 = A.g * riA;
-    const float cB0 = B.g * riB;
-    riA = okA ? riA : 0.f;
-    riB = okB ? riB : 0.f;
-    A.c = okA ? cA0 : 1.f;
-    B.c = okB ? cB0 : 1.f;
-    A.s = fA * riA;
-    B.s = fB * riB;
+    const float riA = __builtin_amdgcn_rsqf(hA);
+    const float riB = __builtin_amdgcn_rsqf(hB);
     const float tA = dk1A - gA;
     const float tB = dk1B - gB;
+    A.c = g0A * riA;
+    B.c = g0B * riB;
+    A.s = fA * riA;
+    B.s = fB * riB;
     const float cbA = 2.f * A.c * bA;
     const float cbB = 2.f * B.c * bB;
     const float r2A = fmaf(tA, A.s, cbA);
@@ -224,7 +244,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
     // lanes own a row slot, so no V access needs a lane predicate (rows >= n are idle lanes).
     constexpr int LD = 65;
     // V, column-major: V[r][c] at sV[c * LD + r]; also the staging buffer for load and store.
-    __shared__ float sV[(N + 2) * LD];
+    __shared__ float sV[(N + 3) * LD];
     // tridiagonal: sP[k] = (e[k-1], d[k]); e[k] couples rows k and k+1
     __shared__ float2 sP[N + 4];
     __shared__ float svec[64];
@@ -249,7 +269,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
             int j = idx - i * n;
             sV[i * LD + j] = Ab[idx];
         }
-        __syncthreads();
+        wave_sync();
         float amax = 0.f;
 #pragma unroll
         for (int c = 0; c < N; ++c) {
@@ -258,7 +278,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
             a[c] = x;
             amax = fmaxf(amax, fabsf(x));   // fmaxf drops NaNs; they still reach the output through the arithmetic
         }
-        __syncthreads();
+        wave_sync();
         float scale;
         pow2_scale(wave_max_nonneg<W>(amax), scale, inv_scale);
 #pragma unroll
@@ -323,7 +343,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
 #pragma unroll
             for (int c = 0; c < N; ++c) sV[c * LD + lane] = v[c];
         }
-        __syncthreads();
+        wave_sync();
     } else {
         // ---- stage hook 2: tridiagonal given ----
         float dv = 0.f, ev = 0.f;
@@ -339,7 +359,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         if (WANT_V) {
             for (int c = 0; c < N; ++c) sV[c * LD + lane] = (c == lane) ? 1.f : 0.f;
         }
-        __syncthreads();
+        wave_sync();
     }
 
     uint32_t rotations = 0;
@@ -366,7 +386,9 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         bool live = lane < n - 1;      // e[lane] not yet deflated
         uint64_t nz = 0;
         float dl = 0.f;
+        BED_PROBE_INIT();
         while (true) {
+            BED_PROBE(0);
             // deflation test, one off-diagonal per lane: lane k looks at e[k], d[k], d[k+1]
             float el = 0.f, dnext = 0.f;
             if (lane < N) {
@@ -383,6 +405,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
             const uint64_t below = ~nz & ((1ull << (hi - 1)) - 1ull);
             const int lo = below ? 64 - __builtin_clzll(below) : 0;
 
+            BED_PROBE(1);
             // eigenvalues of the trailing block [[ta, tb], [tb, td]] (App. A.3), smaller-angle root first
             const float ta = read_lane(dl, hi - 1);
             const float tb = read_lane(el, hi - 1);
@@ -394,28 +417,38 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
             const float mu1 = td - tt;          // eigenvalue closer to the last diagonal entry
             const float mu2 = ta + tt;          // the other eigenvalue of the block
 
+            // Inputs of rotation t: (e[t], d[t+1]) = sP[t+1] and column t+1 of V.  They are
+            // fetched two rotations ahead (qa/ya: rotation t, qb/yb: rotation t+1).
             const float d_lo = read_lane(dl, lo);
-            float ekA = read_lane(el, lo);
-            float dk1A = read_lane(dnext, lo);
-            float2 pn = sP[lo + 2];                 // (e[lo+1], d[lo+2])
-            float ynext = 0.f;
+            float2 qa = make_float2(read_lane(el, lo), read_lane(dnext, lo));
+            float2 qb = sP[lo + 2];
+            float ya = 0.f, yb = 0.f;
             Chain A;
             chain_start<WANT_V>(A, d_lo, mu1, WANT_V ? sV[lo * LD + lane] : 0.f);
-            if (WANT_V) ynext = sV[(lo + 1) * LD + lane];
+            if (WANT_V) {
+                ya = sV[(lo + 1) * LD + lane];
+                yb = sV[(lo + 2) * LD + lane];
+            }
+            // fetch the inputs of rotation t+2 and shift the queue (indices stay inside the padding)
+#define BED_ADVANCE(t_)                                         \
+            do {                                                \
+                const float2 qc_ = sP[(t_) + 3];                \
+                float yc_ = 0.f;                                \
+                if (WANT_V) yc_ = sV[((t_) + 3) * LD + lane];   \
+                qa = qb;                                        \
+                ya = yb;                                        \
+                qb = qc_;                                       \
+                yb = yc_;                                       \
+            } while (0)
 
             if (SHIFT == kShiftSingle) {
                 // one sweep over the window [lo, hi]: rotations k = lo .. hi-1
                 for (int k = lo; k < hi; ++k) {
-                    const float y = ynext;
-                    if (WANT_V) ynext = sV[(k + 2) * LD + lane];   // column k+2 <= N+1 exists (padding)
-                    const float2 pnn = sP[k + 3];                  // (e[k+2], d[k+3]); index <= N+2
                     float eo, dq, vo = 0.f;
-                    chain_rotate<WANT_V>(A, ekA, dk1A, y, eo, dq, vo);
+                    chain_rotate<WANT_V>(A, qa.x, qa.y, ya, eo, dq, vo);
+                    BED_ADVANCE(k);
                     sP[k] = make_float2(eo, dq);
                     if (WANT_V) sV[k * LD + lane] = vo;
-                    ekA = pn.x;
-                    dk1A = pn.y;
-                    pn = pnn;
                 }
                 float eo, dq, vo;
                 chain_finish(A, eo, dq, vo);
@@ -427,61 +460,72 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                 // Two sweeps (shift mu1, then mu2) over the same window, software-pipelined:
                 // sweep B runs two rotations behind sweep A and takes A's results straight
                 // from registers, so the two dependency chains interleave in one
-                // instruction stream.  At iteration t: B handles row t-2 with A's outputs of
-                // iteration t-1, then A handles row t.
-                Chain B;
-                float pE, pD, pV = 0.f;     // A's outputs of the previous iteration
-                auto stepA = [&](int t) {
-                    if (t < hi) {
-                        const float y = ynext;
-                        if (WANT_V) ynext = sV[(t + 2) * LD + lane];
-                        const float2 pnn = sP[t + 3];
-                        chain_rotate<WANT_V>(A, ekA, dk1A, y, pE, pD, pV);
-                        ekA = pn.x;
-                        dk1A = pn.y;
-                        pn = pnn;
-                    } else {
-                        chain_finish(A, pE, pD, pV);
-                    }
-                };
-                auto stepB = [&](int j) {
-                    float eo, dq, vo = 0.f;
-                    if (j < hi) chain_rotate<WANT_V>(B, pE, pD, pV, eo, dq, vo);
-                    else chain_finish(B, eo, dq, vo);
-                    sP[j] = make_float2(eo, dq);
-                    if (WANT_V) sV[j * LD + lane] = vo;
-                };
-                stepA(lo);
-                chain_start<WANT_V>(B, pD, mu2, pV);      // d'[lo], column lo after sweep A
-                stepA(lo + 1);
-                int t = lo + 2;
+                // instruction stream.  At step t: B handles row t-2 with A's outputs of
+                // step t-1, while A handles row t.
+                float pE, pD, pV = 0.f;     // A's outputs of the previous step
+                float eo, dq, vo = 0.f;     // B's outputs
+                BED_PROBE(2);
+                // t = lo: A rotates row lo
+                chain_rotate<WANT_V>(A, qa.x, qa.y, ya, pE, pD, pV);
+                BED_ADVANCE(lo);
+                if (hi - lo == 1) {
+                    // The window is the 2x2 block the shifts were taken from: the step with
+                    // its exact eigenvalue mu1 diagonalises it (this is the rotation of
+                    // App. A.3), so the off-diagonal is set to zero and no second sweep runs.
+                    // (A second sweep here would start from (d'[lo] - mu2, e'[lo]) = rounding
+                    // noise and could rotate the converged block by an arbitrary angle.)
+                    sP[lo] = make_float2(pE, pD);
+                    if (WANT_V) sV[lo * LD + lane] = pV;
+                    chain_finish(A, pE, pD, pV);
+                    sP[hi] = make_float2(0.f, pD);
+                    if (WANT_V) sV[hi * LD + lane] = pV;
+                    rotations += 1u;
+                    sweeps += 1;
+                    BED_PROBE(5);
+                } else {
+                    // B starts from d'[lo] and column lo as left by A
+                    Chain B;
+                    chain_start<WANT_V>(B, pD, mu2, pV);
+                    // t = lo + 1: A rotates row lo+1
+                    chain_rotate<WANT_V>(A, qa.x, qa.y, ya, pE, pD, pV);
+                    BED_ADVANCE(lo + 1);
+                    BED_PROBE(3);
+                    int t = lo + 2;
 #pragma unroll 2
-                for (; t < hi; ++t) {
-                    // steady state: both sweeps rotate; one basic block, two independent chains
-                    float eo, dq, vo = 0.f;
-                    const float y = ynext;
-                    if (WANT_V) ynext = sV[(t + 2) * LD + lane];
-                    const float2 pnn = sP[t + 3];
-                    float nE, nD, nV = 0.f;
-                    chain_rotate2<WANT_V>(A, ekA, dk1A, y, nE, nD, nV, B, pE, pD, pV, eo, dq, vo);
-                    sP[t - 2] = make_float2(eo, dq);
-                    if (WANT_V) sV[(t - 2) * LD + lane] = vo;
-                    pE = nE;
-                    pD = nD;
-                    pV = nV;
-                    ekA = pn.x;
-                    dk1A = pn.y;
-                    pn = pnn;
+                    for (; t < hi; ++t) {
+                        // steady state: A rotates row t, B rotates row t-2; one basic block,
+                        // two independent dependency chains
+                        float nE, nD, nV = 0.f;
+                        chain_rotate2<WANT_V>(A, qa.x, qa.y, ya, nE, nD, nV, B, pE, pD, pV, eo, dq, vo);
+                        BED_ADVANCE(t);
+                        sP[t - 2] = make_float2(eo, dq);
+                        if (WANT_V) sV[(t - 2) * LD + lane] = vo;
+                        pE = nE;
+                        pD = nD;
+                        pV = nV;
+                    }
+                    BED_PROBE(4);
+                    // t = hi: B rotates row hi-2 with A's outputs of row hi-1; A finishes
+                    chain_rotate<WANT_V>(B, pE, pD, pV, eo, dq, vo);
+                    sP[hi - 2] = make_float2(eo, dq);
+                    if (WANT_V) sV[(hi - 2) * LD + lane] = vo;
+                    chain_finish(A, pE, pD, pV);
+                    // t = hi + 1: B rotates row hi-1 with A's closing values; t = hi + 2: B finishes
+                    chain_rotate<WANT_V>(B, pE, pD, pV, eo, dq, vo);
+                    sP[hi - 1] = make_float2(eo, dq);
+                    if (WANT_V) sV[(hi - 1) * LD + lane] = vo;
+                    chain_finish(B, eo, dq, vo);
+                    sP[hi] = make_float2(eo, dq);
+                    if (WANT_V) sV[hi * LD + lane] = vo;
+                    rotations += 2u * (uint32_t)(hi - lo);
+                    sweeps += 2;
+                    BED_PROBE(5);
                 }
-                for (; t - 2 <= hi; ++t) {
-                    stepB(t - 2);
-                    if (t == hi) stepA(t);
-                }
-                rotations += 2u * (uint32_t)(hi - lo);
-                sweeps += 2;
             }
-            __syncthreads();
+#undef BED_ADVANCE
+            wave_sync();
         }
+        BED_PROBE_DUMP();
         info = __builtin_popcountll(nz);
         {
             // a non-finite eigenvalue (NaN/Inf input) is reported even when every off-diagonal deflated
@@ -500,7 +544,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         if (WANT_V) {
             int* sinv = reinterpret_cast<int*>(svec);
             if (lane < n) sinv[rank] = lane;       // output column `rank` comes from column `lane`
-            __syncthreads();
+            wave_sync();
             float* __restrict__ Vb = args.evecs + (size_t)b * n * n;
             const float rcp_n = 1.0f / (float)n;
             for (int idx = lane; idx < n * n; idx += 64) {
