@@ -64,6 +64,13 @@ __device__ __forceinline__ float read_lane(float x, int lane_uniform) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), lane_uniform));
 }
 
+// Every lane receives the value held by lane (i & 31), i.e. the lower half's values are
+// copied over the upper half (v_permlane32_swap of a register with a copy of itself).
+__device__ __forceinline__ float from_lower_half(float x) {
+    const unsigned u = __float_as_uint(x);
+    return __uint_as_float(__builtin_amdgcn_permlane32_swap(u, u, false, false)[0]);
+}
+
 // Sum over lanes [0, W) of the wave (W = 8, 16, 32 or 64, lanes outside must
 // hold 0 or are ignored), returned as a wave-uniform value.  Quad butterflies,
 // then mirrors (which act as xor 4 / xor 8 on quad-uniform values), then row
@@ -137,7 +144,9 @@ __device__ __forceinline__ void chain_start(Chain& S, float d_lo, float mu, floa
 // rounding) so that f^2 + g^2 is always a normal number: the rotation stays
 // exactly normalised and no compare/select sits on the dependency chain.
 __device__ __forceinline__ float guard_g(float g) {
-    const float mag = __builtin_amdgcn_fmed3f(fabsf(g), kTinyG, __builtin_inff());   // max(|g|, floor) in one instruction
+    float mag;
+    // max(|g|, floor) as one VALU instruction (the library fmaxf adds a NaN-quieting step)
+    asm("v_max_f32 %0, |%1|, %2" : "=v"(mag) : "v"(g), "v"(kTinyG));
     return __uint_as_float((__float_as_uint(g) & 0x80000000u) | __float_as_uint(mag));
 }
 
@@ -381,6 +390,11 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         }
     } else {
         // ---- shifted QR iterations on the tridiagonal in sP ----
+        // When the rows fit in half a wavefront, lanes 32..63 shadow rows 0..31: both halves
+        // then own a full copy of the row set and can work on different sweeps (see below).
+        constexpr bool HALF = (N <= 32);
+        const int vrow = HALF ? (lane & 31) : lane;
+        const bool roleB = lane >= 32;
         const uint32_t cap = 30u * (uint32_t)n;
         uint32_t sweeps = 0;
         bool live = lane < n - 1;      // e[lane] not yet deflated
@@ -418,56 +432,58 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
             const float mu2 = ta + tt;          // the other eigenvalue of the block
 
             // Inputs of rotation t: (e[t], d[t+1]) = sP[t+1] and column t+1 of V.  They are
-            // fetched two rotations ahead (qa/ya: rotation t, qb/yb: rotation t+1).
+            // fetched two rotations ahead into two slots used in alternation (slot 0: rotations
+            // lo, lo+2, ...; slot 1: rotations lo+1, lo+3, ...), so a slot is refilled right after
+            // it has been consumed and no register shuffling is needed.
             const float d_lo = read_lane(dl, lo);
-            float2 qa = make_float2(read_lane(el, lo), read_lane(dnext, lo));
-            float2 qb = sP[lo + 2];
-            float ya = 0.f, yb = 0.f;
+            float2 q0 = make_float2(read_lane(el, lo), read_lane(dnext, lo));
+            float2 q1 = sP[lo + 2];
+            float y0 = 0.f, y1 = 0.f;
             Chain A;
-            chain_start<WANT_V>(A, d_lo, mu1, WANT_V ? sV[lo * LD + lane] : 0.f);
+            chain_start<WANT_V>(A, d_lo, mu1, WANT_V ? sV[lo * LD + vrow] : 0.f);
             if (WANT_V) {
-                ya = sV[(lo + 1) * LD + lane];
-                yb = sV[(lo + 2) * LD + lane];
+                y0 = sV[(lo + 1) * LD + vrow];
+                y1 = sV[(lo + 2) * LD + vrow];
             }
-            // fetch the inputs of rotation t+2 and shift the queue (indices stay inside the padding)
-#define BED_ADVANCE(t_)                                         \
+            // refill a slot with the inputs of rotation t_+2 (indices stay inside the padding)
+#define BED_REFILL(q_, y_, t_)                                  \
             do {                                                \
-                const float2 qc_ = sP[(t_) + 3];                \
-                float yc_ = 0.f;                                \
-                if (WANT_V) yc_ = sV[((t_) + 3) * LD + lane];   \
-                qa = qb;                                        \
-                ya = yb;                                        \
-                qb = qc_;                                       \
-                yb = yc_;                                       \
+                q_ = sP[(t_) + 3];                              \
+                if (WANT_V) y_ = sV[((t_) + 3) * LD + vrow];    \
             } while (0)
 
             if (SHIFT == kShiftSingle) {
                 // one sweep over the window [lo, hi]: rotations k = lo .. hi-1
-                for (int k = lo; k < hi; ++k) {
-                    float eo, dq, vo = 0.f;
-                    chain_rotate<WANT_V>(A, qa.x, qa.y, ya, eo, dq, vo);
-                    BED_ADVANCE(k);
-                    sP[k] = make_float2(eo, dq);
-                    if (WANT_V) sV[k * LD + lane] = vo;
+                float eo, dq, vo = 0.f;
+#define BED_STEP1(q_, y_, k_)                                           \
+                do {                                                    \
+                    chain_rotate<WANT_V>(A, q_.x, q_.y, y_, eo, dq, vo); \
+                    BED_REFILL(q_, y_, k_);                             \
+                    sP[k_] = make_float2(eo, dq);                       \
+                    if (WANT_V) sV[(k_) * LD + vrow] = vo;              \
+                } while (0)
+                int k = lo;
+                for (; k + 1 < hi; k += 2) {
+                    BED_STEP1(q0, y0, k);
+                    BED_STEP1(q1, y1, k + 1);
                 }
-                float eo, dq, vo;
+                if (k < hi) BED_STEP1(q0, y0, k);
+#undef BED_STEP1
                 chain_finish(A, eo, dq, vo);
                 sP[hi] = make_float2(eo, dq);
-                if (WANT_V) sV[hi * LD + lane] = vo;
+                if (WANT_V) sV[hi * LD + vrow] = vo;
                 rotations += (uint32_t)(hi - lo);
                 sweeps += 1;
             } else {
                 // Two sweeps (shift mu1, then mu2) over the same window, software-pipelined:
                 // sweep B runs two rotations behind sweep A and takes A's results straight
-                // from registers, so the two dependency chains interleave in one
-                // instruction stream.  At step t: B handles row t-2 with A's outputs of
-                // step t-1, while A handles row t.
+                // from registers.  At step t: B handles row t-2 with A's outputs of step t-1,
+                // while A handles row t.
                 float pE, pD, pV = 0.f;     // A's outputs of the previous step
-                float eo, dq, vo = 0.f;     // B's outputs
                 BED_PROBE(2);
                 // t = lo: A rotates row lo
-                chain_rotate<WANT_V>(A, qa.x, qa.y, ya, pE, pD, pV);
-                BED_ADVANCE(lo);
+                chain_rotate<WANT_V>(A, q0.x, q0.y, y0, pE, pD, pV);
+                BED_REFILL(q0, y0, lo);
                 if (hi - lo == 1) {
                     // The window is the 2x2 block the shifts were taken from: the step with
                     // its exact eigenvalue mu1 diagonalises it (this is the rotation of
@@ -475,54 +491,135 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                     // (A second sweep here would start from (d'[lo] - mu2, e'[lo]) = rounding
                     // noise and could rotate the converged block by an arbitrary angle.)
                     sP[lo] = make_float2(pE, pD);
-                    if (WANT_V) sV[lo * LD + lane] = pV;
+                    if (WANT_V) sV[lo * LD + vrow] = pV;
                     chain_finish(A, pE, pD, pV);
                     sP[hi] = make_float2(0.f, pD);
-                    if (WANT_V) sV[hi * LD + lane] = pV;
+                    if (WANT_V) sV[hi * LD + vrow] = pV;
                     rotations += 1u;
                     sweeps += 1;
                     BED_PROBE(5);
+                } else if (HALF) {
+                    // Role lanes: lanes 0..31 carry sweep A, lanes 32..63 carry sweep B, so one
+                    // instruction stream advances both sweeps by one rotation per step.
+                    // B's inputs are A's outputs of the previous step, copied from the lower
+                    // half of the wavefront.  Only B's results are stored; A lanes store to a
+                    // dump slot.
+                    const float sD = pD, sX = pV;              // d'[lo], column lo as left by A
+                    // t = lo + 1: A rotates row lo+1 (still computed by every lane)
+                    chain_rotate<WANT_V>(A, q1.x, q1.y, y1, pE, pD, pV);
+                    BED_REFILL(q1, y1, lo + 1);
+                    BED_PROBE(3);
+                    Chain S;                                   // this lane's chain: A or B
+                    S.g = roleB ? (sD - mu2) : A.g;
+                    S.s = roleB ? 1.f : A.s;
+                    S.c = roleB ? 1.f : A.c;
+                    S.p = roleB ? 0.f : A.p;
+                    S.dk = roleB ? sD : A.dk;
+                    S.x = roleB ? sX : A.x;
+                    float inE = pE, inD = pD, inV = pV;        // B's inputs: A's outputs of step lo+1
+                    // store addresses (in floats): B lanes walk rows lo, lo+1, ...; A lanes stay on the dump
+                    int wP = roleB ? 2 * lo : 2 * (N + 3);
+                    int wV = (roleB ? lo : (N + 2)) * LD + vrow;
+                    const int incP = roleB ? 2 : 0;
+                    const int incV = roleB ? LD : 0;
+                    float* sPf = reinterpret_cast<float*>(sP);
+                    float oE, oD, oV = 0.f;
+#define BED_STEPH(q_, y_, t_)                                                       \
+                    do {                                                            \
+                        const float e_in = roleB ? inE : q_.x;                      \
+                        const float d_in = roleB ? inD : q_.y;                      \
+                        const float y_in = roleB ? inV : y_;                        \
+                        chain_rotate<WANT_V>(S, e_in, d_in, y_in, oE, oD, oV);      \
+                        BED_REFILL(q_, y_, t_);                                     \
+                        *reinterpret_cast<float2*>(sPf + wP) = make_float2(oE, oD); \
+                        if (WANT_V) sV[wV] = oV;                                    \
+                        wP += incP;                                                 \
+                        wV += incV;                                                 \
+                        inE = from_lower_half(oE);                                  \
+                        inD = from_lower_half(oD);                                  \
+                        if (WANT_V) inV = from_lower_half(oV);                      \
+                    } while (0)
+                    int t = lo + 2;
+                    for (; t + 1 < hi; t += 2) {
+                        BED_STEPH(q0, y0, t);
+                        BED_STEPH(q1, y1, t + 1);
+                    }
+                    if (t < hi) BED_STEPH(q0, y0, t);
+#undef BED_STEPH
+                    BED_PROBE(4);
+                    // t = hi: A closes (values taken before its state is overwritten); B rotates row hi-2
+                    float fE, fD, fV;
+                    chain_finish(S, fE, fD, fV);
+                    chain_rotate<WANT_V>(S, inE, inD, inV, oE, oD, oV);
+                    *reinterpret_cast<float2*>(sPf + wP) = make_float2(oE, oD);
+                    if (WANT_V) sV[wV] = oV;
+                    wP += incP;
+                    wV += incV;
+                    // t = hi + 1: B rotates row hi-1 with A's closing values
+                    inE = from_lower_half(fE);
+                    inD = from_lower_half(fD);
+                    if (WANT_V) inV = from_lower_half(fV);
+                    chain_rotate<WANT_V>(S, inE, inD, inV, oE, oD, oV);
+                    *reinterpret_cast<float2*>(sPf + wP) = make_float2(oE, oD);
+                    if (WANT_V) sV[wV] = oV;
+                    wP += incP;
+                    wV += incV;
+                    // t = hi + 2: B closes
+                    chain_finish(S, fE, fD, fV);
+                    *reinterpret_cast<float2*>(sPf + wP) = make_float2(fE, fD);
+                    if (WANT_V) sV[wV] = fV;
+                    rotations += 2u * (uint32_t)(hi - lo);
+                    sweeps += 2;
+                    BED_PROBE(5);
                 } else {
+                    // Rows need the whole wavefront: both chains are computed by every lane,
+                    // interleaved statement by statement.
                     // B starts from d'[lo] and column lo as left by A
                     Chain B;
                     chain_start<WANT_V>(B, pD, mu2, pV);
                     // t = lo + 1: A rotates row lo+1
-                    chain_rotate<WANT_V>(A, qa.x, qa.y, ya, pE, pD, pV);
-                    BED_ADVANCE(lo + 1);
+                    chain_rotate<WANT_V>(A, q1.x, q1.y, y1, pE, pD, pV);
+                    BED_REFILL(q1, y1, lo + 1);
                     BED_PROBE(3);
+                    float eo, dq, vo = 0.f;     // B's outputs
+#define BED_STEP2(q_, y_, t_)                                                                    \
+                    do {                                                                         \
+                        float nE, nD, nV = 0.f;                                                  \
+                        chain_rotate2<WANT_V>(A, q_.x, q_.y, y_, nE, nD, nV, B, pE, pD, pV, eo, dq, vo); \
+                        BED_REFILL(q_, y_, t_);                                                  \
+                        sP[(t_) - 2] = make_float2(eo, dq);                                      \
+                        if (WANT_V) sV[((t_) - 2) * LD + vrow] = vo;                             \
+                        pE = nE;                                                                 \
+                        pD = nD;                                                                 \
+                        pV = nV;                                                                 \
+                    } while (0)
                     int t = lo + 2;
-#pragma unroll 2
-                    for (; t < hi; ++t) {
-                        // steady state: A rotates row t, B rotates row t-2; one basic block,
-                        // two independent dependency chains
-                        float nE, nD, nV = 0.f;
-                        chain_rotate2<WANT_V>(A, qa.x, qa.y, ya, nE, nD, nV, B, pE, pD, pV, eo, dq, vo);
-                        BED_ADVANCE(t);
-                        sP[t - 2] = make_float2(eo, dq);
-                        if (WANT_V) sV[(t - 2) * LD + lane] = vo;
-                        pE = nE;
-                        pD = nD;
-                        pV = nV;
+                    for (; t + 1 < hi; t += 2) {
+                        // steady state: A rotates row t, B rotates row t-2
+                        BED_STEP2(q0, y0, t);
+                        BED_STEP2(q1, y1, t + 1);
                     }
+                    if (t < hi) BED_STEP2(q0, y0, t);
+#undef BED_STEP2
                     BED_PROBE(4);
                     // t = hi: B rotates row hi-2 with A's outputs of row hi-1; A finishes
                     chain_rotate<WANT_V>(B, pE, pD, pV, eo, dq, vo);
                     sP[hi - 2] = make_float2(eo, dq);
-                    if (WANT_V) sV[(hi - 2) * LD + lane] = vo;
+                    if (WANT_V) sV[(hi - 2) * LD + vrow] = vo;
                     chain_finish(A, pE, pD, pV);
                     // t = hi + 1: B rotates row hi-1 with A's closing values; t = hi + 2: B finishes
                     chain_rotate<WANT_V>(B, pE, pD, pV, eo, dq, vo);
                     sP[hi - 1] = make_float2(eo, dq);
-                    if (WANT_V) sV[(hi - 1) * LD + lane] = vo;
+                    if (WANT_V) sV[(hi - 1) * LD + vrow] = vo;
                     chain_finish(B, eo, dq, vo);
                     sP[hi] = make_float2(eo, dq);
-                    if (WANT_V) sV[hi * LD + lane] = vo;
+                    if (WANT_V) sV[hi * LD + vrow] = vo;
                     rotations += 2u * (uint32_t)(hi - lo);
                     sweeps += 2;
                     BED_PROBE(5);
                 }
             }
-#undef BED_ADVANCE
+#undef BED_REFILL
             wave_sync();
         }
         BED_PROBE_DUMP();
