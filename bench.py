@@ -50,6 +50,11 @@ def main(argv=None) -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workload", default="headline", choices=["headline"])
+    ap.add_argument("--only-n", type=int, default=0,
+                    help="profiling aid: launch only the batch-512 call of this n, --steps times, and exit")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="profiling aid: run a plain device-to-device copy of MIB mebibytes --steps times and exit "
+                         "(reference reading for the FETCH_SIZE / WRITE_SIZE counters)")
     a = ap.parse_args(argv)
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the batch is embarrassingly parallel; "
@@ -67,7 +72,30 @@ def main(argv=None) -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if a.copy_calibration:
+        nbytes = a.copy_calibration << 20
+        src = torch.empty(nbytes // 4, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(a.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": nbytes, "launches": a.steps}))
+        return 0
+
     points = workloads.headline_points()          # [(n, A32)], batch 512 each
+    if a.only_n:
+        points = [pt for pt in points if pt[0] == a.only_n]
+        n, A32 = points[0]
+        A = torch.from_numpy(A32).to(dev)
+        ev = torch.empty((A.shape[0], n), dtype=torch.float32, device=dev)
+        V = torch.empty((A.shape[0], n, n), dtype=torch.float32, device=dev)
+        torch.cuda.synchronize()
+        for _ in range(a.steps):
+            binding.bed_syevd(A, ev, V)
+        torch.cuda.synchronize()
+        print(json.dumps({"only_n": n, "launches": a.steps, "batch": int(A.shape[0])}))
+        return 0
     bufs = []
     for n, A32 in points:
         A = torch.from_numpy(A32).to(dev)
@@ -139,13 +167,15 @@ def main(argv=None) -> int:
         per_n[str(n)]["matrices_per_s_back_to_back"] = int(A.shape[0]) * a.steps / (tb - ta)
 
     dom = per_n["32"]
+    # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary
+    # (FETCH_SIZE + WRITE_SIZE scaled by a plain copy of known size); null if it is absent.
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic_n32_b512.json")
+    tpath = os.path.join(ROOT, "profiles", "wave_kernel_n32_b512_counters.md")
     if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
-        except Exception:
-            traffic = None
+        import re
+        m = re.search(r"^hbm_bytes_per_launch:\s*([0-9.]+)", open(tpath).read(), flags=re.M)
+        if m:
+            traffic = float(m.group(1))
     roofline = {
         "kernel": "bed::wave_kernel<32> (n=32, batch 512)",
         "bound": "alu",

@@ -669,20 +669,17 @@ static hipError_t launch_one(const KernelArgs& args, hipStream_t stream) {
 
 template <int N>
 static hipError_t launch_n(const KernelArgs& args, int stage, int shift, bool want_v, hipStream_t stream) {
+    // Only the paper's double shift is instantiated; kShiftSingle stays in the source
+    // as the reference single-sweep loop for experiments.
+    (void)shift;
     if (stage == kTridiagOnly) {
         return want_v ? launch_one<N, true, kTridiagOnly, kShiftDouble>(args, stream)
                       : launch_one<N, false, kTridiagOnly, kShiftDouble>(args, stream);
     }
     if (stage == kQrOnly) {
-        if (shift == kShiftSingle)
-            return want_v ? launch_one<N, true, kQrOnly, kShiftSingle>(args, stream)
-                          : launch_one<N, false, kQrOnly, kShiftSingle>(args, stream);
         return want_v ? launch_one<N, true, kQrOnly, kShiftDouble>(args, stream)
                       : launch_one<N, false, kQrOnly, kShiftDouble>(args, stream);
     }
-    if (shift == kShiftSingle)
-        return want_v ? launch_one<N, true, kFull, kShiftSingle>(args, stream)
-                      : launch_one<N, false, kFull, kShiftSingle>(args, stream);
     return want_v ? launch_one<N, true, kFull, kShiftDouble>(args, stream)
                   : launch_one<N, false, kFull, kShiftDouble>(args, stream);
 }
