@@ -257,6 +257,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
     // tridiagonal: sP[k] = (e[k-1], d[k]); e[k] couples rows k and k+1
     __shared__ float2 sP[N + 4];
     __shared__ float svec[64];
+    __shared__ float sq[64];
 
     const int lane = threadIdx.x;
     const int b = blockIdx.x;
@@ -296,6 +297,15 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         // ---- Householder tridiagonalisation, column J reduced at step J ----
         // Branch-free: a step that has nothing to do (J >= n-2, or the column is
         // already reduced) runs with u = 0 and beta = 0.
+        // u and q are broadcast through LDS (one write, then 128-bit reads that every lane
+        // issues for the same address); the latency of each round trip is covered by
+        // independent work: the rank-1 update of V is deferred by one step and runs while
+        // the next u is in flight, and the part of the rank-2 update of A that needs only
+        // this lane's q runs while q is in flight.
+        float ud[N];          // u of the previous step (for the deferred update of V)
+        float wd = 0.f;       // its 2 V u / |u|^2
+#pragma unroll
+        for (int c = 0; c < N; ++c) ud[c] = 0.f;
 #pragma unroll
         for (int J = 0; J < N; ++J) {
             const float dJ = read_lane(a[J], J);      // final once columns 0..J-1 are reduced
@@ -314,31 +324,38 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                     const float beta = active ? __builtin_amdgcn_rcpf(fmaf(fabsf(x0), nrm, alpha)) : 0.f;  // 2/|u|^2
                     eJ = active ? -sigma : x0;
                     svec[lane] = ur;
+                    if (WANT_V && J > 0) {
+                        // deferred: V <- V - w u^T of step J-1 (columns J .. N-1)
+#pragma unroll
+                        for (int c = J; c < N; ++c) v[c] = fmaf(-wd, ud[c], v[c]);
+                    }
                     __syncthreads();
                     float u[N];
 #pragma unroll
                     for (int c = J + 1; c < N; ++c) u[c] = svec[c];
-                    __syncthreads();
-                    float p = 0.f, w = 0.f;
+                    // p = 2 A u / |u|^2, w = 2 V u / |u|^2; four partial sums each
+                    float pp[4] = {0.f, 0.f, 0.f, 0.f}, ww[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int c = J + 1; c < N; ++c) {
-                        p = fmaf(a[c], u[c], p);
-                        if (WANT_V) w = fmaf(v[c], u[c], w);
+                        pp[c & 3] = fmaf(a[c], u[c], pp[c & 3]);
+                        if (WANT_V) ww[c & 3] = fmaf(v[c], u[c], ww[c & 3]);
                     }
-                    p *= beta;                                    // p = 2 A u / |u|^2
-                    w *= beta;
+                    const float p = beta * ((pp[0] + pp[1]) + (pp[2] + pp[3]));
+                    wd = beta * ((ww[0] + ww[1]) + (ww[2] + ww[3]));
                     const float K = 0.5f * beta * wave_sum<W>(ur * p);
                     const float q = fmaf(-K, ur, p);              // q = p - K u (symmetric rank-2 form)
-                    svec[lane] = q;
+                    sq[lane] = q;
+#pragma unroll
+                    for (int c = J + 1; c < N; ++c) a[c] = fmaf(-q, u[c], a[c]);
                     __syncthreads();
 #pragma unroll
                     for (int c = J + 1; c < N; ++c) {
-                        const float qc = svec[c];
-                        a[c] = fmaf(-q, u[c], a[c]);
-                        a[c] = fmaf(-ur, qc, a[c]);
-                        if (WANT_V) v[c] = fmaf(-w, u[c], v[c]);
+                        a[c] = fmaf(-ur, sq[c], a[c]);
+                        ud[c] = u[c];
                     }
-                    __syncthreads();
+                    // keep the steps apart: interleaving them makes the compiler hoist the next
+                    // steps' loads and run out of registers
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
             // sP[J+1].x = e[J], sP[J].y = d[J]
@@ -346,6 +363,11 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                 sP[J].y = dJ;
                 sP[J + 1].x = (J < n - 1) ? eJ : 0.f;
             }
+        }
+        if (WANT_V && N > 2) {
+            // the last reflector's deferred update of V
+#pragma unroll
+            for (int c = N - 2; c < N; ++c) v[c] = fmaf(-wd, ud[c], v[c]);
         }
         if (lane == 0) sP[0].x = 0.f;
         if (WANT_V) {
