@@ -253,9 +253,17 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
     // lanes own a row slot, so no V access needs a lane predicate (rows >= n are idle lanes).
     constexpr int LD = 65;
     // V, column-major: V[r][c] at sV[c * LD + r]; also the staging buffer for load and store.
-    __shared__ float sV[(N + 3) * LD];
+    // For N <= 32 the arrays are flanked by a sink area on each side: the role-lane loop
+    // addresses LDS through one running pointer per lane, and the lanes of the role that
+    // has nothing to load (or store) land in a sink instead of needing a predicate.
+    constexpr bool HALF = (N <= 32);
+    constexpr int VA = (N + 6) * LD;           // floats in one V area (columns 0..N-1 plus look-ahead padding)
+    constexpr int PA = N + 8;                  // float2 entries in one T area
+    __shared__ float sV_all[HALF ? 3 * VA : VA];
+    __shared__ float2 sP_all[HALF ? 3 * PA : PA];
+    float* const sV = sV_all + (HALF ? VA : 0);
     // tridiagonal: sP[k] = (e[k-1], d[k]); e[k] couples rows k and k+1
-    __shared__ float2 sP[N + 4];
+    float2* const sP = sP_all + (HALF ? PA : 0);
     __shared__ float svec[64];
     __shared__ float sq[64];
 
@@ -414,7 +422,6 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         // ---- shifted QR iterations on the tridiagonal in sP ----
         // When the rows fit in half a wavefront, lanes 32..63 shadow rows 0..31: both halves
         // then own a full copy of the row set and can work on different sweeps (see below).
-        constexpr bool HALF = (N <= 32);
         const int vrow = HALF ? (lane & 31) : lane;
         const bool roleB = lane >= 32;
         const uint32_t cap = 30u * (uint32_t)n;
@@ -538,58 +545,62 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                     S.p = roleB ? 0.f : A.p;
                     S.dk = roleB ? sD : A.dk;
                     S.x = roleB ? sX : A.x;
-                    float inE = pE, inD = pD, inV = pV;        // B's inputs: A's outputs of step lo+1
-                    // store addresses (in floats): B lanes walk rows lo, lo+1, ...; A lanes stay on the dump
-                    int wP = roleB ? 2 * lo : 2 * (N + 3);
-                    int wV = (roleB ? lo : (N + 2)) * LD + vrow;
-                    const int incP = roleB ? 2 : 0;
-                    const int incV = roleB ? LD : 0;
-                    float* sPf = reinterpret_cast<float*>(sP);
+                    // B's inputs: A's outputs of the previous step.  e and d are uniform over the A
+                    // lanes and travel through a scalar register; the V entry is per row and is
+                    // copied from the lower half.
+                    float inE = pE, inD = pD, inV = pV;
+                    // One running LDS pointer per lane and array.  A lanes: it points at the
+                    // inputs of rotation t+2 (loads are real, stores at +area land in the upper
+                    // sink).  B lanes: it points one area below the row they store (loads come
+                    // from the lower sink and are ignored, stores at +area are real).
+                    const float* xV = sV + (roleB ? (lo * LD - VA) : (lo + 5) * LD) + vrow;
+                    const float2* xP = sP + (roleB ? (lo - PA) : (lo + 5));
                     float oE, oD, oV = 0.f;
-#define BED_STEPH(q_, y_, t_)                                                       \
+#define BED_STEPH(q_, y_, k_)                                                       \
                     do {                                                            \
                         const float e_in = roleB ? inE : q_.x;                      \
                         const float d_in = roleB ? inD : q_.y;                      \
                         const float y_in = roleB ? inV : y_;                        \
                         chain_rotate<WANT_V>(S, e_in, d_in, y_in, oE, oD, oV);      \
-                        BED_REFILL(q_, y_, t_);                                     \
-                        *reinterpret_cast<float2*>(sPf + wP) = make_float2(oE, oD); \
-                        if (WANT_V) sV[wV] = oV;                                    \
-                        wP += incP;                                                 \
-                        wV += incV;                                                 \
-                        inE = from_lower_half(oE);                                  \
-                        inD = from_lower_half(oD);                                  \
+                        q_ = xP[(k_)];                                              \
+                        if (WANT_V) y_ = xV[(k_) * LD];                             \
+                        const_cast<float2*>(xP)[(k_) + PA] = make_float2(oE, oD);   \
+                        if (WANT_V) const_cast<float*>(xV)[(k_) * LD + VA] = oV;    \
+                        inE = read_lane(oE, 0);                                     \
+                        inD = read_lane(oD, 0);                                     \
                         if (WANT_V) inV = from_lower_half(oV);                      \
                     } while (0)
                     int t = lo + 2;
                     for (; t + 1 < hi; t += 2) {
-                        BED_STEPH(q0, y0, t);
-                        BED_STEPH(q1, y1, t + 1);
+                        BED_STEPH(q0, y0, 0);
+                        BED_STEPH(q1, y1, 1);
+                        xV += 2 * LD;
+                        xP += 2;
                     }
-                    if (t < hi) BED_STEPH(q0, y0, t);
+                    if (t < hi) {
+                        BED_STEPH(q0, y0, 0);
+                        xV += LD;
+                        xP += 1;
+                    }
 #undef BED_STEPH
                     BED_PROBE(4);
                     // t = hi: A closes (values taken before its state is overwritten); B rotates row hi-2
                     float fE, fD, fV;
                     chain_finish(S, fE, fD, fV);
                     chain_rotate<WANT_V>(S, inE, inD, inV, oE, oD, oV);
-                    *reinterpret_cast<float2*>(sPf + wP) = make_float2(oE, oD);
-                    if (WANT_V) sV[wV] = oV;
-                    wP += incP;
-                    wV += incV;
+                    const_cast<float2*>(xP)[PA] = make_float2(oE, oD);
+                    if (WANT_V) const_cast<float*>(xV)[VA] = oV;
                     // t = hi + 1: B rotates row hi-1 with A's closing values
-                    inE = from_lower_half(fE);
-                    inD = from_lower_half(fD);
+                    inE = read_lane(fE, 0);
+                    inD = read_lane(fD, 0);
                     if (WANT_V) inV = from_lower_half(fV);
                     chain_rotate<WANT_V>(S, inE, inD, inV, oE, oD, oV);
-                    *reinterpret_cast<float2*>(sPf + wP) = make_float2(oE, oD);
-                    if (WANT_V) sV[wV] = oV;
-                    wP += incP;
-                    wV += incV;
+                    const_cast<float2*>(xP)[PA + 1] = make_float2(oE, oD);
+                    if (WANT_V) const_cast<float*>(xV)[VA + LD] = oV;
                     // t = hi + 2: B closes
                     chain_finish(S, fE, fD, fV);
-                    *reinterpret_cast<float2*>(sPf + wP) = make_float2(fE, fD);
-                    if (WANT_V) sV[wV] = fV;
+                    const_cast<float2*>(xP)[PA + 2] = make_float2(fE, fD);
+                    if (WANT_V) const_cast<float*>(xV)[VA + 2 * LD] = fV;
                     rotations += 2u * (uint32_t)(hi - lo);
                     sweeps += 2;
                     BED_PROBE(5);
