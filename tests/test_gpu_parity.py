@@ -212,3 +212,76 @@ def test_non_default_stream():
     st.synchronize()
     lam_o, _ = jacobi.syevd(A)
     assert np.abs(ev.cpu().numpy() - lam_o).max() <= 1e-5 * np.abs(lam_o).max()
+
+
+# --- very large batches of tiny matrices: the one-matrix-per-lane kernels ------
+
+def test_config2_full_batch_65536():
+    """Config 2 at its largest batch (n = 4, batch 65536), every matrix checked."""
+    from paper_2207_04228_amd import workloads
+    _check(workloads.config2(65536), "config2_b65536")
+
+
+@pytest.mark.parametrize("n,batch", [(1, 8200), (2, 8192 + 37), (3, 9001), (4, 8192), (5, 16384 + 63),
+                                     (7, 16385), (8, 20000)])
+def test_lane_kernels_ragged_batches(n, batch):
+    """Batches that do not fill the last wavefront, all n the lane kernels serve, indefinite input."""
+    rng = np.random.default_rng(7000 + 10 * n)
+    A = rng.standard_normal((batch, n, n))
+    A = (0.5 * (A + A.transpose(0, 2, 1))).astype(np.float32)
+    _check(A, f"lane_n{n}_b{batch}")
+
+
+def test_lane_kernel_agrees_with_wave_kernel():
+    """The same matrices through both kernel families (batch above / below the dispatch
+    threshold) must give the same decomposition to rounding."""
+    from oracle.acceptance import evaluate
+    from paper_2207_04228_amd import workloads
+    A = workloads.config2(65536)[:8192]
+    lam_lane, V_lane = _solve_gpu(A)            # batch 8192: lane kernel
+    lam_wave, V_wave = _solve_gpu(A[:4096])     # batch 4096: wave kernel
+    acc = evaluate(A[:4096], lam_lane[:4096], V_lane[:4096], lam_wave.astype(np.float64), V_wave.astype(np.float64))
+    w = acc.worst()
+    assert w["eval_err"] <= 2e-6 and w["angle"] <= 1e-3, w
+
+
+def test_lane_kernel_degenerate_and_nan():
+    """Diagonal / zero / NaN matrices inside a lane-kernel batch: exact results for the
+    exact cases, NaN confined to its own matrix, info set."""
+    import torch
+    from paper_2207_04228_amd import binding, workloads
+    A = workloads.config2(65536)[:8192].copy()
+    A[5] = np.diag([3.0, -1.0, 2.0, 2.0]).astype(np.float32)
+    A[6] = 0.0
+    A[7] = np.eye(4, dtype=np.float32)
+    A[70, 2, 1] = np.nan
+    ev, V, info, rot = binding.bed_syevd_info(torch.from_numpy(A).to("cuda:0"))
+    torch.cuda.synchronize()
+    ev, V, info = ev.cpu().numpy(), V.cpu().numpy(), info.cpu().numpy()
+    assert np.array_equal(ev[5], np.array([-1.0, 2.0, 2.0, 3.0], dtype=np.float32))
+    assert np.array_equal(ev[6], np.zeros(4, dtype=np.float32))
+    assert np.array_equal(ev[7], np.ones(4, dtype=np.float32))
+    assert info[70] > 0 and not np.isfinite(ev[70]).all()
+    good = np.ones(8192, dtype=bool); good[70] = False
+    assert np.isfinite(ev[good]).all() and np.isfinite(V[good]).all() and np.all(info[good] == 0)
+
+
+# --- properties at the full benchmark sizes (launch configuration of bench.py) -------
+
+def test_headline_sizes_sampled_against_oracle_and_invariants():
+    """Batch 512 at n = 4, 8, 16, 32 exactly as bench.py launches them: every matrix's trace
+    and Frobenius invariants, plus a sample of matrices checked entry by entry."""
+    from oracle import jacobi
+    from oracle.acceptance import evaluate
+    from paper_2207_04228_amd import workloads
+    for n, A in workloads.headline_points():
+        lam, V = _solve_gpu(A)
+        A64 = A.astype(np.float64)
+        tr = np.trace(A64, axis1=1, axis2=2)
+        fro2 = (A64 * A64).sum(axis=(1, 2))
+        assert np.all(np.abs(lam.astype(np.float64).sum(axis=1) - tr) <= 1e-5 * n * np.sqrt(fro2))
+        assert np.all(np.abs((lam.astype(np.float64) ** 2).sum(axis=1) - fro2) <= 2e-5 * n * fro2)
+        idx = np.arange(0, 512, 37)
+        lo, Vo = jacobi.syevd(A[idx])
+        acc = evaluate(A[idx], lam[idx], V[idx], lo, Vo)
+        assert acc.passes(), (n, acc.worst())
