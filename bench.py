@@ -49,6 +49,8 @@ def main(argv=None) -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the untimed extra measurements (eigenvalues only, spectral function, large batches)")
     ap.add_argument("--workload", default="headline", choices=["headline"])
     ap.add_argument("--only-n", type=int, default=0,
                     help="profiling aid: launch only the batch-512 call of this n, --steps times, and exit")
@@ -166,6 +168,37 @@ def main(argv=None) -> int:
         tb = time.perf_counter()
         per_n[str(n)]["matrices_per_s_back_to_back"] = int(A.shape[0]) * a.steps / (tb - ta)
 
+    # ---- extras (outside the timed region; reported, not part of `value`) ----
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    extras = {"eigenvalues_only_us": {}, "spd_inv_sqrt_us": {}, "large_batch": {}}
+    reps = max(10, a.steps // 4)
+    for n, A, ev, V in ([] if a.no_extras else bufs):
+        F = torch.empty_like(V)
+        ev2 = torch.empty_like(ev)
+        extras["eigenvalues_only_us"][str(n)] = timed(lambda: binding.bed_syevd(A, ev2, None, want_vectors=False), reps) * 1e6
+        extras["spd_inv_sqrt_us"][str(n)] = timed(
+            lambda: binding.bed_spd_fn(A, binding.BED_FN_INV_SQRT, 1e-6, out=F), reps) * 1e6
+    for n, batch in (() if a.no_extras else ((4, 65536), (8, 65536), (16, 4096), (32, 4096))):
+        Ab = torch.from_numpy(workloads.config2(batch) if n == 4 else workloads.config3(n, batch=batch)).to(dev)
+        evb = torch.empty((batch, n), dtype=torch.float32, device=dev)
+        Vb = torch.empty((batch, n, n), dtype=torch.float32, device=dev)
+        t = timed(lambda: binding.bed_syevd(Ab, evb, Vb), 10)
+        extras["large_batch"][f"n{n}_b{batch}"] = {
+            "kernel_us": t * 1e6, "matrices_per_s": batch / t,
+            "gbs": batch * bytes_per_matrix(n) / t / 1e9}
+        del Ab, evb, Vb
+
     dom = per_n["32"]
     # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary
     # (FETCH_SIZE + WRITE_SIZE scaled by a plain copy of known size); null if it is absent.
@@ -233,6 +266,7 @@ def main(argv=None) -> int:
                                "(config 2 at batch 512, config 3 at n = 8, 16, 32); one step = 4 calls = 2048 matrices",
                    "batch": 512, "dims": [4, 8, 16, 32], "eigenvectors": True},
         "per_n": per_n,
+        "extras": None if a.no_extras else extras,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "parity": parity,

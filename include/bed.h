@@ -33,8 +33,14 @@ typedef enum {
     BED_ERR_N = -3,      /* n < 1 or n > BED_MAX_N                          */
     BED_ERR_ALIGN = -4,  /* a pointer is not 4-byte aligned                 */
     BED_ERR_LAUNCH = -5, /* the HIP runtime refused the launch              */
-    BED_ERR_ALIAS = -6   /* an output buffer overlaps the input             */
+    BED_ERR_ALIAS = -6,  /* an output buffer overlaps the input             */
+    BED_ERR_ARG = -7     /* an enumerated or scalar argument is out of range */
 } bed_status;
+
+typedef enum {
+    BED_FN_SQRT = 0,     /* f(x) = x^(1/2)                                  */
+    BED_FN_INV_SQRT = 1  /* f(x) = x^(-1/2)                                 */
+} bed_fn;
 
 /*
  * Eigendecomposition A_b = V_b diag(lambda_b) V_b^T of `batch` symmetric
@@ -91,6 +97,26 @@ int bed_tridiag(const float* A, int batch, int n, float* d, float* e, float* P,
 int bed_tridiag_qr(const float* d, const float* e, int batch, int n,
                    float* evals, float* evecs, int* info, unsigned* rotations,
                    void* stream);
+
+/*
+ * Fused spectral function of a batch of symmetric positive (semi-)definite
+ * matrices: out_b = V_b f(max(Lambda_b, floor)) V_b^T, computed from the
+ * eigendecomposition inside the same launch, without writing V.  This is what
+ * the paper's applications do right after the decomposition: A^(-1/2) for ZCA
+ * whitening / decorrelated batch normalisation and the whitening half of the
+ * whitening-and-colouring transform, A^(1/2) for covariance pooling and the
+ * colouring half (Sec. 4.2, 4.3, 4.4; App. B.1, B.2, B.3).
+ *
+ *   A      device, const, [batch][n][n] fp32, lower triangle read (as bed_syevd)
+ *   fn     BED_FN_SQRT or BED_FN_INV_SQRT
+ *   floor  eigenvalues below it are raised to it before f is applied; must be
+ *          finite and >= 0, and > 0 for BED_FN_INV_SQRT (BED_ERR_ARG otherwise)
+ *   out    device, [batch][n][n] row-major fp32, symmetric
+ *   evals  device, [batch][n] ascending eigenvalues of A (not floored), or NULL
+ *   info   device, [batch] as in bed_syevd_info, or NULL
+ */
+int bed_spd_fn(const float* A, int batch, int n, int fn, float floor, float* out,
+               float* evals, int* info, void* stream);
 
 /* Human-readable name of a bed_status value (static storage). */
 const char* bed_status_string(int status);

@@ -5,7 +5,10 @@ The library is loaded lazily on first use; importing this package never
 touches the GPU.
 """
 from .binding import (  # noqa: F401
+    BED_FN_INV_SQRT,
+    BED_FN_SQRT,
     BedError,
+    bed_spd_fn,
     bed_syevd,
     bed_syevd_info,
     bed_tridiag,

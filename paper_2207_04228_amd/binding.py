@@ -45,6 +45,8 @@ def load_library():
         lib.bed_tridiag.restype = ci
         lib.bed_tridiag_qr.argtypes = [vp, vp, ci, ci, vp, vp, vp, vp, vp]
         lib.bed_tridiag_qr.restype = ci
+        lib.bed_spd_fn.argtypes = [vp, ci, ci, ci, ctypes.c_float, vp, vp, vp, vp]
+        lib.bed_spd_fn.restype = ci
         lib.bed_status_string.argtypes = [ci]
         lib.bed_status_string.restype = ctypes.c_char_p
         lib.bed_version.argtypes = []
@@ -157,3 +159,27 @@ def bed_tridiag_qr(d, e, *, want_vectors=True, stream=None):
     if st != 0:
         raise BedError(st, "bed_tridiag_qr")
     return evals, evecs, info, rot
+
+
+BED_FN_SQRT = 0
+BED_FN_INV_SQRT = 1
+
+
+def bed_spd_fn(A, fn, floor, out=None, *, want_evals=False, stream=None):
+    """out_b = V_b f(max(Lambda_b, floor)) V_b^T for fn in {BED_FN_SQRT, BED_FN_INV_SQRT}.
+    Returns (out [batch, n, n], evals or None, info int32 [batch])."""
+    import torch
+    _check_dev(A, "A", torch.float32)
+    batch, n, n2 = A.shape
+    if n != n2:
+        raise ValueError("A must be [batch, n, n]")
+    if out is None:
+        out = torch.empty((batch, n, n), dtype=torch.float32, device=A.device)
+    _check_dev(out, "out", torch.float32)
+    evals = torch.empty((batch, n), dtype=torch.float32, device=A.device) if want_evals else None
+    info = torch.empty((batch,), dtype=torch.int32, device=A.device)
+    st = load_library().bed_spd_fn(_ptr(A), batch, n, int(fn), float(floor), _ptr(out), _ptr(evals),
+                                   _ptr(info), _stream(stream))
+    if st != 0:
+        raise BedError(st, "bed_spd_fn")
+    return out, evals, info

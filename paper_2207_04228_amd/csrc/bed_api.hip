@@ -102,6 +102,31 @@ int bed_tridiag_qr(const float* d, const float* e, int batch, int n, float* eval
     return run(args, bed::kQrOnly, evecs != nullptr, stream);
 }
 
+int bed_spd_fn(const float* A, int batch, int n, int fn, float floor, float* out, float* evals, int* info,
+               void* stream) {
+    int st = check_common(batch, n);
+    if (st != BED_OK) return st;
+    if (fn != BED_FN_SQRT && fn != BED_FN_INV_SQRT) return BED_ERR_ARG;
+    if (!(floor >= 0.f) || !(floor < __builtin_inff())) return BED_ERR_ARG;
+    if (fn == BED_FN_INV_SQRT && !(floor > 0.f)) return BED_ERR_ARG;
+    if (batch == 0) return BED_OK;
+    if (!A || !out) return BED_ERR_NULL;
+    if (misaligned(A) || misaligned(out) || misaligned(evals) || misaligned(info)) return BED_ERR_ALIGN;
+    const size_t mat = (size_t)batch * n * n * sizeof(float), vec = (size_t)batch * n * sizeof(float);
+    if (overlaps(A, mat, out, mat) || overlaps(A, mat, evals, vec) || overlaps(out, mat, evals, vec))
+        return BED_ERR_ALIAS;
+    bed::KernelArgs args{};
+    args.A = A;
+    args.fn_out = out;
+    args.fn = (fn == BED_FN_INV_SQRT) ? bed::kFnInvSqrt : bed::kFnSqrt;
+    args.fn_floor = floor;
+    args.evals = evals;
+    args.info = info;
+    args.batch = batch;
+    args.n = n;
+    return run(args, bed::kSpectral, true, stream);
+}
+
 const char* bed_status_string(int status) {
     switch (status) {
         case BED_OK: return "BED_OK";
@@ -111,6 +136,7 @@ const char* bed_status_string(int status) {
         case BED_ERR_ALIGN: return "BED_ERR_ALIGN: pointers must be 4-byte aligned";
         case BED_ERR_LAUNCH: return "BED_ERR_LAUNCH: kernel launch failed";
         case BED_ERR_ALIAS: return "BED_ERR_ALIAS: buffers overlap";
+        case BED_ERR_ARG: return "BED_ERR_ARG: argument out of range";
         default: return "BED_ERR_UNKNOWN";
     }
 }

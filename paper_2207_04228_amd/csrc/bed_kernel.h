@@ -7,7 +7,8 @@
 
 namespace bed {
 
-enum Stage { kFull = 0, kTridiagOnly = 1, kQrOnly = 2 };
+enum Stage { kFull = 0, kTridiagOnly = 1, kQrOnly = 2, kSpectral = 3 };
+enum SpectralFn { kFnSqrt = 0, kFnInvSqrt = 1 };
 enum ShiftPolicy { kShiftDouble = 0, kShiftSingle = 1 };
 
 struct KernelArgs {
@@ -18,6 +19,9 @@ struct KernelArgs {
     float* evecs;        // [batch][n][n] or P       (when vectors are wanted)
     float* d_out;        // [batch][n]               (kTridiagOnly)
     float* e_out;        // [batch][n]               (kTridiagOnly)
+    float* fn_out;       // [batch][n][n]            (kSpectral) V f(lambda) V^T
+    float fn_floor;      // eigenvalues are raised to this floor before f is applied (kSpectral)
+    int fn;              // SpectralFn (kSpectral)
     int* info;           // [batch] or nullptr
     uint32_t* rotations; // [batch] or nullptr
     int batch;

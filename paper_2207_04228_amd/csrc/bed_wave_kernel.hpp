@@ -663,6 +663,45 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
             info = max(info, (int)__builtin_popcountll(bad));
         }
 
+        if (STAGE == kSpectral) {
+            // ---- F = V f(Lambda) V^T (Sec. 4.2-4.4, App. B: A^{-1/2} for whitening, A^{1/2} for
+            // covariance pooling / colouring), straight from V and lambda in LDS; no sort needed.
+            // Lane r forms w[k] = V[r][k] f(lambda_k) once, then F[r][c] = sum_k w[k] V[c][k] for
+            // every c; F is symmetric, so the entry is stored at F[c][r] and consecutive lanes
+            // write consecutive addresses.  With rows shadowed in both halves of the wavefront
+            // (n <= 32) the halves split the columns.
+            const int row = HALF ? (lane & 31) : lane;
+            float w[N];
+#pragma unroll
+            for (int k = 0; k < N; ++k) {
+                float lam = sP[k].y * inv_scale;
+                lam = fmaxf(lam, args.fn_floor);
+                const float fl = (args.fn == kFnInvSqrt) ? __builtin_amdgcn_rsqf(lam) : __builtin_amdgcn_sqrtf(lam);
+                w[k] = (k < n) ? sV[k * LD + row] * fl : 0.f;
+            }
+            float* __restrict__ Fb = args.fn_out + (size_t)b * n * n;
+            const int c0 = HALF ? (lane >> 5) : 0;
+            const int cstep = HALF ? 2 : 1;
+            for (int c = c0; c < n; c += cstep) {
+                float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int k = 0; k < N; ++k) acc[k & 3] = fmaf(w[k], sV[k * LD + c], acc[k & 3]);
+                if (row < n) Fb[c * n + row] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+            }
+            if (args.evals) {
+                // eigenvalues as a by-product (ascending)
+                const uint32_t key = sort_key(dl);
+                int rk = 0;
+                for (int j = 0; j < n; ++j) {
+                    const uint32_t kj = sort_key(sP[j].y);
+                    rk += (kj < key || (kj == key && j < lane)) ? 1 : 0;
+                }
+                if (lane < n) args.evals[(size_t)b * n + rk] = dl * inv_scale;
+            }
+            if (lane == 0 && args.info) args.info[b] = info;
+            return;
+        }
+
         // ---- ascending order: rank of d[lane] among d[0..n) ----
         const uint32_t mykey = sort_key(dl);
         int rank = 0;
@@ -713,6 +752,7 @@ static hipError_t launch_n(const KernelArgs& args, int stage, int shift, bool wa
         return want_v ? launch_one<N, true, kQrOnly, kShiftDouble>(args, stream)
                       : launch_one<N, false, kQrOnly, kShiftDouble>(args, stream);
     }
+    if (stage == kSpectral) return launch_one<N, true, kSpectral, kShiftDouble>(args, stream);
     return want_v ? launch_one<N, true, kFull, kShiftDouble>(args, stream)
                   : launch_one<N, false, kFull, kShiftDouble>(args, stream);
 }

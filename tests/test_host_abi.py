@@ -28,7 +28,7 @@ def _declared_symbols():
 
 def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
-    assert {"bed_syevd", "bed_syevd_info", "bed_tridiag", "bed_tridiag_qr",
+    assert {"bed_syevd", "bed_syevd_info", "bed_tridiag", "bed_tridiag_qr", "bed_spd_fn",
             "bed_status_string", "bed_version"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
@@ -37,7 +37,7 @@ def test_header_symbols_are_exported(lib):
 def test_version_and_status_strings(lib):
     assert binding.bed_version() == 100
     assert binding.bed_status_string(0) == "BED_OK"
-    for code in (-1, -2, -3, -4, -5, -6):
+    for code in (-1, -2, -3, -4, -5, -6, -7):
         assert binding.bed_status_string(code).startswith("BED_ERR_")
     assert "UNKNOWN" in binding.bed_status_string(-99)
 
@@ -58,6 +58,17 @@ def test_argument_validation_is_host_side(lib):
     assert lib.bed_tridiag_qr(A, None, 1, 4, L, V, None, None, None) == -1
     assert lib.bed_tridiag_qr(A, L, 0, 4, V, None, None, None, None) == 0
     assert lib.bed_syevd_info(A, 1, 4, L, V, p(0x40001), None, None) == -4
+    f = ctypes.c_float
+    assert lib.bed_spd_fn(None, 1, 4, 0, f(0.0), V, None, None, None) == -1        # NULL A
+    assert lib.bed_spd_fn(A, 1, 4, 0, f(0.0), None, None, None, None) == -1        # NULL out
+    assert lib.bed_spd_fn(A, 1, 4, 2, f(1.0), V, None, None, None) == -7           # unknown function
+    assert lib.bed_spd_fn(A, 1, 4, 1, f(0.0), V, None, None, None) == -7           # inverse sqrt, floor 0
+    assert lib.bed_spd_fn(A, 1, 4, 0, f(-1.0), V, None, None, None) == -7          # negative floor
+    assert lib.bed_spd_fn(A, 1, 4, 0, f(float("nan")), V, None, None, None) == -7  # NaN floor
+    assert lib.bed_spd_fn(A, 1, 4, 0, f(float("inf")), V, None, None, None) == -7  # infinite floor
+    assert lib.bed_spd_fn(A, 1, 65, 0, f(0.0), V, None, None, None) == -3
+    assert lib.bed_spd_fn(A, 1, 4, 0, f(0.0), p(0x10020), None, None, None) == -6  # out overlaps A
+    assert lib.bed_spd_fn(A, 0, 4, 0, f(0.0), V, None, None, None) == 0
 
 
 def test_binding_rejects_cpu_tensors():
