@@ -249,25 +249,26 @@ __device__ __forceinline__ void chain_finish(const Chain& S, float& e_out, float
 template <int N, bool WANT_V, int STAGE, int SHIFT>
 __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
     constexpr int W = lanes_for(N);
-    // Column stride 65: odd (conflict-free rows and columns) and wide enough that all 64
-    // lanes own a row slot, so no V access needs a lane predicate (rows >= n are idle lanes).
-    constexpr int LD = 65;
-    // V, column-major: V[r][c] at sV[c * LD + r]; also the staging buffer for load and store.
-    // For N <= 32 the arrays are flanked by a sink area on each side: the role-lane loop
-    // addresses LDS through one running pointer per lane, and the lanes of the role that
-    // has nothing to load (or store) land in a sink instead of needing a predicate.
+    // When the rows fit in half a wavefront (N <= 32), lanes 32..63 shadow rows 0..31 from
+    // load to store: both halves hold the same row data, and in the QR phase they carry the
+    // two sweeps of an iteration.
     constexpr bool HALF = (N <= 32);
-    constexpr int VA = (N + 6) * LD;           // floats in one V area (columns 0..N-1 plus look-ahead padding)
-    constexpr int PA = N + 8;                  // float2 entries in one T area
-    __shared__ float sV_all[HALF ? 3 * VA : VA];
-    __shared__ float2 sP_all[HALF ? 3 * PA : PA];
-    float* const sV = sV_all + (HALF ? VA : 0);
+    // Column stride: odd (conflict-free rows and columns) and wide enough that every lane
+    // owns a row slot, so no V access needs a lane predicate (rows >= n are idle lanes).
+    constexpr int LD = HALF ? 33 : 65;
+    // V, column-major: V[r][c] at sV[c * LD + r]; also the staging buffer for load and store.
+    // Columns N .. N+7 and entries N .. N+9 of the tridiagonal are padding: the QR loop reads
+    // up to three positions ahead of the window and parks idle stores there.
+    constexpr int VA = (N + 8) * LD;
+    constexpr int PA = N + 10;
+    __shared__ float sV[VA];
     // tridiagonal: sP[k] = (e[k-1], d[k]); e[k] couples rows k and k+1
-    float2* const sP = sP_all + (HALF ? PA : 0);
+    __shared__ float2 sP[PA];
     __shared__ float svec[64];
     __shared__ float sq[64];
 
     const int lane = threadIdx.x;
+    const int row = HALF ? (lane & 31) : lane;     // the row of the matrix and of V this lane owns
     const int b = blockIdx.x;
     const int n = args.n;
 
@@ -277,9 +278,9 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         float a[N];
         float v[N];
 #pragma unroll
-        for (int c = 0; c < N; ++c) v[c] = (c == lane) ? 1.f : 0.f;
+        for (int c = 0; c < N; ++c) v[c] = (c == row) ? 1.f : 0.f;
 
-        // ---- load: coalesced into LDS, then row `lane` (lower triangle mirrored)
+        // ---- load: coalesced into LDS, then row `row` (lower triangle mirrored)
         const float* __restrict__ Ab = args.A + (size_t)b * n * n;
         const float rcp_n = 1.0f / (float)n;
         for (int idx = lane; idx < n * n; idx += 64) {
@@ -292,7 +293,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
 #pragma unroll
         for (int c = 0; c < N; ++c) {
             float x = 0.f;
-            if (lane < n && c < n) x = (c <= lane) ? sV[lane * LD + c] : sV[c * LD + lane];
+            if (row < n && c < n) x = (c <= row) ? sV[row * LD + c] : sV[c * LD + row];
             a[c] = x;
             amax = fmaxf(amax, fabsf(x));   // fmaxf drops NaNs; they still reach the output through the arithmetic
         }
@@ -322,12 +323,12 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                 const float x0 = read_lane(a[J], J + 1);     // A[J+1][J]
                 eJ = x0;                                      // kept as is when no reflector is applied
                 if (J < N - 2) {
-                    const float x = (lane > J) ? a[J] : 0.f;  // A[r][J], r > J
+                    const float x = (row > J) ? a[J] : 0.f;   // A[r][J], r > J
                     const float alpha = wave_sum<W>(x * x);   // |x|^2
                     const bool active = (J < n - 2) && (alpha > kTinyAlpha);
                     const float nrm = __builtin_amdgcn_sqrtf(alpha);
                     const float sigma = (x0 < 0.f) ? -nrm : nrm;   // sign chosen to avoid cancellation
-                    float ur = (lane == J + 1) ? (x0 + sigma) : ((lane > J + 1) ? x : 0.f);
+                    float ur = (row == J + 1) ? (x0 + sigma) : ((row > J + 1) ? x : 0.f);
                     ur = active ? ur : 0.f;
                     const float beta = active ? __builtin_amdgcn_rcpf(fmaf(fabsf(x0), nrm, alpha)) : 0.f;  // 2/|u|^2
                     eJ = active ? -sigma : x0;
@@ -380,7 +381,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         if (lane == 0) sP[0].x = 0.f;
         if (WANT_V) {
 #pragma unroll
-            for (int c = 0; c < N; ++c) sV[c * LD + lane] = v[c];
+            for (int c = 0; c < N; ++c) sV[c * LD + row] = v[c];
         }
         wave_sync();
     } else {
@@ -396,7 +397,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         }
         if (lane == 0) sP[0].x = 0.f;
         if (WANT_V) {
-            for (int c = 0; c < N; ++c) sV[c * LD + lane] = (c == lane) ? 1.f : 0.f;
+            for (int c = 0; c < N; ++c) sV[c * LD + row] = (c == row) ? 1.f : 0.f;
         }
         wave_sync();
     }
@@ -420,9 +421,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         }
     } else {
         // ---- shifted QR iterations on the tridiagonal in sP ----
-        // When the rows fit in half a wavefront, lanes 32..63 shadow rows 0..31: both halves
-        // then own a full copy of the row set and can work on different sweeps (see below).
-        const int vrow = HALF ? (lane & 31) : lane;
+        const int vrow = row;
         const bool roleB = lane >= 32;
         const uint32_t cap = 30u * (uint32_t)n;
         uint32_t sweeps = 0;
@@ -549,12 +548,15 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                     // lanes and travel through a scalar register; the V entry is per row and is
                     // copied from the lower half.
                     float inE = pE, inD = pD, inV = pV;
-                    // One running LDS pointer per lane and array.  A lanes: it points at the
-                    // inputs of rotation t+2 (loads are real, stores at +area land in the upper
-                    // sink).  B lanes: it points one area below the row they store (loads come
-                    // from the lower sink and are ignored, stores at +area are real).
-                    const float* xV = sV + (roleB ? (lo * LD - VA) : (lo + 5) * LD) + vrow;
-                    const float2* xP = sP + (roleB ? (lo - PA) : (lo + 5));
+                    // One running LDS pointer per lane and array; every lane stores at the pointer
+                    // and loads three positions above it.  A lanes: the pointer is at position t,
+                    // so the load fetches the inputs of rotation t+2 (position t+3) and the store
+                    // lands on a position A has already consumed and B overwrites with the final
+                    // value two steps later.  B lanes: the pointer is at position t-2, so the
+                    // store is the real one and the load is a valid address whose value is ignored.
+                    constexpr int AHEAD = 3;
+                    const float* xV = sV + (roleB ? lo : (lo + 2)) * LD + vrow;
+                    const float2* xP = sP + (roleB ? lo : (lo + 2));
                     float oE, oD, oV = 0.f;
 #define BED_STEPH(q_, y_, k_)                                                       \
                     do {                                                            \
@@ -562,10 +564,10 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                         const float d_in = roleB ? inD : q_.y;                      \
                         const float y_in = roleB ? inV : y_;                        \
                         chain_rotate<WANT_V>(S, e_in, d_in, y_in, oE, oD, oV);      \
-                        q_ = xP[(k_)];                                              \
-                        if (WANT_V) y_ = xV[(k_) * LD];                             \
-                        const_cast<float2*>(xP)[(k_) + PA] = make_float2(oE, oD);   \
-                        if (WANT_V) const_cast<float*>(xV)[(k_) * LD + VA] = oV;    \
+                        q_ = xP[(k_) + AHEAD];                                      \
+                        if (WANT_V) y_ = xV[((k_) + AHEAD) * LD];                   \
+                        const_cast<float2*>(xP)[(k_)] = make_float2(oE, oD);        \
+                        if (WANT_V) const_cast<float*>(xV)[(k_) * LD] = oV;         \
                         inE = read_lane(oE, 0);                                     \
                         inD = read_lane(oD, 0);                                     \
                         if (WANT_V) inV = from_lower_half(oV);                      \
@@ -584,23 +586,27 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                     }
 #undef BED_STEPH
                     BED_PROBE(4);
+                    // The three closing steps belong to B alone; the A lanes' stores would now land
+                    // beyond the window, so they are parked in the padding behind the arrays.
+                    xV = roleB ? xV : (sV + (N + 3) * LD + vrow);
+                    xP = roleB ? xP : (sP + (N + 3));
                     // t = hi: A closes (values taken before its state is overwritten); B rotates row hi-2
                     float fE, fD, fV;
                     chain_finish(S, fE, fD, fV);
                     chain_rotate<WANT_V>(S, inE, inD, inV, oE, oD, oV);
-                    const_cast<float2*>(xP)[PA] = make_float2(oE, oD);
-                    if (WANT_V) const_cast<float*>(xV)[VA] = oV;
+                    const_cast<float2*>(xP)[0] = make_float2(oE, oD);
+                    if (WANT_V) const_cast<float*>(xV)[0] = oV;
                     // t = hi + 1: B rotates row hi-1 with A's closing values
                     inE = read_lane(fE, 0);
                     inD = read_lane(fD, 0);
                     if (WANT_V) inV = from_lower_half(fV);
                     chain_rotate<WANT_V>(S, inE, inD, inV, oE, oD, oV);
-                    const_cast<float2*>(xP)[PA + 1] = make_float2(oE, oD);
-                    if (WANT_V) const_cast<float*>(xV)[VA + LD] = oV;
+                    const_cast<float2*>(xP)[1] = make_float2(oE, oD);
+                    if (WANT_V) const_cast<float*>(xV)[LD] = oV;
                     // t = hi + 2: B closes
                     chain_finish(S, fE, fD, fV);
-                    const_cast<float2*>(xP)[PA + 2] = make_float2(fE, fD);
-                    if (WANT_V) const_cast<float*>(xV)[VA + 2 * LD] = fV;
+                    const_cast<float2*>(xP)[2] = make_float2(fE, fD);
+                    if (WANT_V) const_cast<float*>(xV)[2 * LD] = fV;
                     rotations += 2u * (uint32_t)(hi - lo);
                     sweeps += 2;
                     BED_PROBE(5);
@@ -670,7 +676,6 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
             // every c; F is symmetric, so the entry is stored at F[c][r] and consecutive lanes
             // write consecutive addresses.  With rows shadowed in both halves of the wavefront
             // (n <= 32) the halves split the columns.
-            const int row = HALF ? (lane & 31) : lane;
             float w[N];
 #pragma unroll
             for (int k = 0; k < N; ++k) {
