@@ -181,7 +181,8 @@ def main(argv=None) -> int:
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e-3 / reps
 
-    extras = {"eigenvalues_only_us": {}, "spd_inv_sqrt_us": {}, "large_batch": {}}
+    extras = {"eigenvalues_only_us": {}, "spd_inv_sqrt_us": {}, "syevd_backward_taylor9_us": {},
+              "spd_inv_sqrt_backward_us": {}, "large_batch": {}}
     reps = max(10, a.steps // 4)
     for n, A, ev, V in ([] if a.no_extras else bufs):
         F = torch.empty_like(V)
@@ -189,6 +190,13 @@ def main(argv=None) -> int:
         extras["eigenvalues_only_us"][str(n)] = timed(lambda: binding.bed_syevd(A, ev2, None, want_vectors=False), reps) * 1e6
         extras["spd_inv_sqrt_us"][str(n)] = timed(
             lambda: binding.bed_spd_fn(A, binding.BED_FN_INV_SQRT, 1e-6, out=F), reps) * 1e6
+        gl = torch.ones_like(ev)
+        gV = torch.ones_like(V)
+        extras["syevd_backward_taylor9_us"][str(n)] = timed(
+            lambda: binding.bed_syevd_backward(ev, V, gl, gV, mode=binding.BED_GRAD_TAYLOR, degree=9, grad_A=F),
+            reps) * 1e6
+        extras["spd_inv_sqrt_backward_us"][str(n)] = timed(
+            lambda: binding.bed_spd_fn_backward(ev, V, gV, binding.BED_FN_INV_SQRT, 1e-6, grad_A=F), reps) * 1e6
     for n, batch in (() if a.no_extras else ((4, 65536), (8, 65536), (16, 4096), (32, 4096))):
         Ab = torch.from_numpy(workloads.config2(batch) if n == 4 else workloads.config3(n, batch=batch)).to(dev)
         evb = torch.empty((batch, n), dtype=torch.float32, device=dev)

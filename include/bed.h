@@ -118,6 +118,57 @@ int bed_tridiag_qr(const float* d, const float* e, int batch, int n,
 int bed_spd_fn(const float* A, int batch, int n, int fn, float floor, float* out,
                float* evals, int* info, void* stream);
 
+typedef enum {
+    BED_GRAD_EXACT = 0,  /* K_ij = 1/(lambda_j - lambda_i) where |lambda_j - lambda_i| >= gap_floor, else 0 */
+    BED_GRAD_TAYLOR = 1  /* K_ij replaced by its truncated geometric series of the given degree          */
+} bed_grad_mode;
+
+/*
+ * Gradient through the eigendecomposition A = V diag(lambda) V^T (Sec. 3.1 Eq. (1)): for a
+ * loss with upstream gradients grad_evals (dL/dlambda) and grad_evecs (dL/dV),
+ *
+ *   grad_A = V ( diag(grad_evals) + sym( K o (V^T grad_evecs) ) ) V^T,   K_ii = 0,
+ *
+ * the symmetric gradient with respect to A (first-order perturbation theory).  The paper
+ * does not derive a backward pass of its own; it uses a Taylor polynomial of degree 9 in
+ * place of 1/(lambda_i - lambda_j), which stays finite for close and repeated eigenvalues
+ * (Sec. 2; App. B "Implementation Details" and App. B.1).  BED_GRAD_TAYLOR is that choice:
+ * for the pair (a, b) = (lambda_i, lambda_j) with b the larger in magnitude (for equal
+ * magnitudes: the later index), K_ij = (1/b) sum_{k=0}^{degree} (a/b)^k, mirrored with the
+ * opposite sign otherwise, so that K is antisymmetric and finite for repeated eigenvalues.  BED_GRAD_EXACT is the unmodified coupling
+ * with pairs closer than gap_floor (absolute) dropped.
+ *
+ *   evals, evecs     device, const, [batch][n] and [batch][n][n] as written by bed_syevd
+ *   grad_evals       device, const, [batch][n], or NULL (taken as zero)
+ *   grad_evecs       device, const, [batch][n][n], or NULL (taken as zero); not both NULL
+ *   mode, degree, gap_floor   see above; degree in 0..64 (BED_GRAD_TAYLOR), gap_floor finite
+ *                    and >= 0 (BED_GRAD_EXACT); the unused one is ignored
+ *   grad_A           device, [batch][n][n] row-major fp32; may alias none of the inputs
+ */
+int bed_syevd_backward(const float* evals, const float* evecs, const float* grad_evals,
+                       const float* grad_evecs, int batch, int n, int mode, int degree,
+                       float gap_floor, float* grad_A, void* stream);
+
+/*
+ * Gradient through bed_spd_fn: for F = V f(max(Lambda, floor)) V^T (Sec. 4.2-4.4, App.
+ * B.1-B.3) and an upstream gradient grad_out = dL/dF,
+ *
+ *   grad_A = V ( Phi o (V^T sym(grad_out) V) ) V^T,
+ *   Phi_ij = (f~(lambda_i) - f~(lambda_j)) / (lambda_i - lambda_j),  f~(x) = f(max(x, floor)),
+ *
+ * with the derivative of f~ where the two eigenvalues coincide.  For eigenvalues above the
+ * floor the divided difference is evaluated without cancellation (1/(s_i + s_j) for the
+ * square root, -1/(s_i s_j (s_i + s_j)) for the inverse square root, s = sqrt(lambda)), so
+ * close and repeated eigenvalues need no special treatment.
+ *
+ *   evals, evecs   device, const, eigendecomposition of A as written by bed_syevd
+ *   grad_out       device, const, [batch][n][n] (need not be symmetric)
+ *   fn, floor      as in bed_spd_fn
+ *   grad_A         device, [batch][n][n]; may alias none of the inputs
+ */
+int bed_spd_fn_backward(const float* evals, const float* evecs, const float* grad_out, int batch,
+                        int n, int fn, float floor, float* grad_A, void* stream);
+
 /* Human-readable name of a bed_status value (static storage). */
 const char* bed_status_string(int status);
 

@@ -43,12 +43,16 @@ def coupling_exact(lam: np.ndarray, gap_floor: float, decide_in_float32: bool = 
 
 
 def coupling_taylor(lam: np.ndarray, degree: int) -> np.ndarray:
-    """K_ij for the pair (a, b) = (lam_i, lam_j): with |b| >= |a|,
+    """K_ij for the pair (a, b) = (lam_i, lam_j): with b the larger in magnitude,
     1/(b - a) = (1/b) / (1 - a/b) is replaced by (1/b) sum_{k=0}^{degree} (a/b)^k;
-    with |b| < |a| by -(1/a) sum_k (b/a)^k.  Finite for equal eigenvalues."""
-    a = np.broadcast_to(lam[..., :, None], lam.shape + (lam.shape[-1],))
-    b = np.broadcast_to(lam[..., None, :], lam.shape + (lam.shape[-1],))
-    big_b = np.abs(b) >= np.abs(a)
+    otherwise by -(1/a) sum_k (b/a)^k.  Finite for equal eigenvalues; for equal magnitudes
+    the one with the larger index counts as the larger (the eigenvalues are sorted), so
+    that K stays antisymmetric like the exact coupling."""
+    n = lam.shape[-1]
+    a = np.broadcast_to(lam[..., :, None], lam.shape + (n,))
+    b = np.broadcast_to(lam[..., None, :], lam.shape + (n,))
+    later = np.arange(n)[None, :] > np.arange(n)[:, None]            # j > i
+    big_b = (np.abs(b) > np.abs(a)) | ((np.abs(b) == np.abs(a)) & later)
     num = np.where(big_b, a, b)
     den = np.where(big_b, b, a)
     K = np.zeros(a.shape)
@@ -60,7 +64,6 @@ def coupling_taylor(lam: np.ndarray, degree: int) -> np.ndarray:
         s = s + rho ** k
     K[ok] = s[ok] / den[ok]
     K = np.where(big_b, K, -K)
-    n = lam.shape[-1]
     K[..., np.arange(n), np.arange(n)] = 0.0
     return K
 

@@ -6,9 +6,13 @@ touches the GPU.
 """
 from .binding import (  # noqa: F401
     BED_FN_INV_SQRT,
+    BED_GRAD_EXACT,
+    BED_GRAD_TAYLOR,
     BED_FN_SQRT,
     BedError,
     bed_spd_fn,
+    bed_spd_fn_backward,
+    bed_syevd_backward,
     bed_syevd,
     bed_syevd_info,
     bed_tridiag,

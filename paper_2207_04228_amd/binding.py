@@ -47,6 +47,10 @@ def load_library():
         lib.bed_tridiag_qr.restype = ci
         lib.bed_spd_fn.argtypes = [vp, ci, ci, ci, ctypes.c_float, vp, vp, vp, vp]
         lib.bed_spd_fn.restype = ci
+        lib.bed_syevd_backward.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ctypes.c_float, vp, vp]
+        lib.bed_syevd_backward.restype = ci
+        lib.bed_spd_fn_backward.argtypes = [vp, vp, vp, ci, ci, ci, ctypes.c_float, vp, vp]
+        lib.bed_spd_fn_backward.restype = ci
         lib.bed_status_string.argtypes = [ci]
         lib.bed_status_string.restype = ctypes.c_char_p
         lib.bed_version.argtypes = []
@@ -183,3 +187,50 @@ def bed_spd_fn(A, fn, floor, out=None, *, want_evals=False, stream=None):
     if st != 0:
         raise BedError(st, "bed_spd_fn")
     return out, evals, info
+
+
+BED_GRAD_EXACT = 0
+BED_GRAD_TAYLOR = 1
+
+
+def bed_syevd_backward(evals, evecs, grad_evals=None, grad_evecs=None, *, mode=BED_GRAD_TAYLOR, degree=9,
+                       gap_floor=0.0, grad_A=None, stream=None):
+    """grad_A = V (diag(grad_evals) + sym(K o (V^T grad_evecs))) V^T, the gradient with respect to A."""
+    import torch
+    _check_dev(evals, "evals", torch.float32)
+    _check_dev(evecs, "evecs", torch.float32)
+    batch, n, n2 = evecs.shape
+    if n != n2 or tuple(evals.shape) != (batch, n):
+        raise ValueError("evals must be [batch, n] and evecs [batch, n, n]")
+    for t, name, shape in ((grad_evals, "grad_evals", (batch, n)), (grad_evecs, "grad_evecs", (batch, n, n))):
+        if t is not None:
+            _check_dev(t, name, torch.float32)
+            if tuple(t.shape) != shape:
+                raise ValueError(f"{name} must have shape {shape}")
+    if grad_A is None:
+        grad_A = torch.empty((batch, n, n), dtype=torch.float32, device=evecs.device)
+    _check_dev(grad_A, "grad_A", torch.float32)
+    st = load_library().bed_syevd_backward(_ptr(evals), _ptr(evecs), _ptr(grad_evals), _ptr(grad_evecs), batch, n,
+                                           int(mode), int(degree), float(gap_floor), _ptr(grad_A), _stream(stream))
+    if st != 0:
+        raise BedError(st, "bed_syevd_backward")
+    return grad_A
+
+
+def bed_spd_fn_backward(evals, evecs, grad_out, fn, floor, *, grad_A=None, stream=None):
+    """Gradient of <grad_out, V f(max(Lambda, floor)) V^T> with respect to A."""
+    import torch
+    _check_dev(evals, "evals", torch.float32)
+    _check_dev(evecs, "evecs", torch.float32)
+    _check_dev(grad_out, "grad_out", torch.float32)
+    batch, n, n2 = evecs.shape
+    if n != n2 or tuple(evals.shape) != (batch, n) or tuple(grad_out.shape) != (batch, n, n):
+        raise ValueError("evals must be [batch, n]; evecs and grad_out [batch, n, n]")
+    if grad_A is None:
+        grad_A = torch.empty((batch, n, n), dtype=torch.float32, device=evecs.device)
+    _check_dev(grad_A, "grad_A", torch.float32)
+    st = load_library().bed_spd_fn_backward(_ptr(evals), _ptr(evecs), _ptr(grad_out), batch, n, int(fn),
+                                            float(floor), _ptr(grad_A), _stream(stream))
+    if st != 0:
+        raise BedError(st, "bed_spd_fn_backward")
+    return grad_A

@@ -127,6 +127,61 @@ int bed_spd_fn(const float* A, int batch, int n, int fn, float floor, float* out
     return run(args, bed::kSpectral, true, stream);
 }
 
+int bed_syevd_backward(const float* evals, const float* evecs, const float* grad_evals, const float* grad_evecs,
+                       int batch, int n, int mode, int degree, float gap_floor, float* grad_A, void* stream) {
+    int st = check_common(batch, n);
+    if (st != BED_OK) return st;
+    if (mode != BED_GRAD_EXACT && mode != BED_GRAD_TAYLOR) return BED_ERR_ARG;
+    if (mode == BED_GRAD_TAYLOR && (degree < 0 || degree > 64)) return BED_ERR_ARG;
+    if (mode == BED_GRAD_EXACT && (!(gap_floor >= 0.f) || !(gap_floor < __builtin_inff()))) return BED_ERR_ARG;
+    if (batch == 0) return BED_OK;
+    if (!evals || !evecs || !grad_A || (!grad_evals && !grad_evecs)) return BED_ERR_NULL;
+    if (misaligned(evals) || misaligned(evecs) || misaligned(grad_evals) || misaligned(grad_evecs) ||
+        misaligned(grad_A))
+        return BED_ERR_ALIGN;
+    const size_t mat = (size_t)batch * n * n * sizeof(float), vec = (size_t)batch * n * sizeof(float);
+    if (overlaps(grad_A, mat, evals, vec) || overlaps(grad_A, mat, evecs, mat) ||
+        overlaps(grad_A, mat, grad_evals, vec) || overlaps(grad_A, mat, grad_evecs, mat))
+        return BED_ERR_ALIAS;
+    bed::GradArgs args{};
+    args.evals = evals;
+    args.evecs = evecs;
+    args.g_evals = grad_evals;
+    args.g_mat = grad_evecs;
+    args.g_A = grad_A;
+    args.batch = batch;
+    args.n = n;
+    args.mode = (mode == BED_GRAD_TAYLOR) ? bed::kGradTaylor : bed::kGradExact;
+    args.degree = degree;
+    args.param = gap_floor;
+    return bed::launch_grad(args, static_cast<hipStream_t>(stream)) == hipSuccess ? BED_OK : BED_ERR_LAUNCH;
+}
+
+int bed_spd_fn_backward(const float* evals, const float* evecs, const float* grad_out, int batch, int n, int fn,
+                        float floor, float* grad_A, void* stream) {
+    int st = check_common(batch, n);
+    if (st != BED_OK) return st;
+    if (fn != BED_FN_SQRT && fn != BED_FN_INV_SQRT) return BED_ERR_ARG;
+    if (!(floor >= 0.f) || !(floor < __builtin_inff())) return BED_ERR_ARG;
+    if (fn == BED_FN_INV_SQRT && !(floor > 0.f)) return BED_ERR_ARG;
+    if (batch == 0) return BED_OK;
+    if (!evals || !evecs || !grad_out || !grad_A) return BED_ERR_NULL;
+    if (misaligned(evals) || misaligned(evecs) || misaligned(grad_out) || misaligned(grad_A)) return BED_ERR_ALIGN;
+    const size_t mat = (size_t)batch * n * n * sizeof(float), vec = (size_t)batch * n * sizeof(float);
+    if (overlaps(grad_A, mat, evals, vec) || overlaps(grad_A, mat, evecs, mat) || overlaps(grad_A, mat, grad_out, mat))
+        return BED_ERR_ALIAS;
+    bed::GradArgs args{};
+    args.evals = evals;
+    args.evecs = evecs;
+    args.g_mat = grad_out;
+    args.g_A = grad_A;
+    args.batch = batch;
+    args.n = n;
+    args.mode = (fn == BED_FN_INV_SQRT) ? bed::kGradInvSqrt : bed::kGradSqrt;
+    args.param = floor;
+    return bed::launch_grad(args, static_cast<hipStream_t>(stream)) == hipSuccess ? BED_OK : BED_ERR_LAUNCH;
+}
+
 const char* bed_status_string(int status) {
     switch (status) {
         case BED_OK: return "BED_OK";

@@ -1,0 +1,216 @@
+// Gradients through the eigendecomposition on the matrix cores (gfx950, wave64).
+//
+// For A = V diag(lambda) V^T (Sec. 3.1 Eq. (1)) and a loss with upstream
+// gradients g_lambda, g_V, first-order perturbation theory gives
+//   g_A = V ( diag(g_lambda) + sym(K o (V^T g_V)) ) V^T,  K_ij = 1/(lambda_j - lambda_i),
+// where the coupling K is either exact with a gap floor or replaced by its
+// truncated geometric series (the Taylor polynomial the paper uses for the
+// backward pass, App. B / App. B.1: degree 9).  For F = V f(max(Lambda, floor)) V^T
+// (Sec. 4.2-4.4, App. B.1-B.3) the same structure holds with divided
+// differences of f in place of K:
+//   g_A = V ( Phi o (V^T sym(G) V) ) V^T.
+//
+// One wavefront owns one matrix.  The three (four) n x n x n products are dense
+// contractions and run on v_mfma_f32_32x32x2_f32 (full fp32 operands and
+// accumulation); operands are staged in LDS with an odd row stride so that row
+// and column (transposed) operand reads are both conflict-free, and every
+// product's result is written back to LDS in row-major order to become an
+// operand of the next one.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "bed_kernel.h"
+
+namespace bed {
+
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ void wave_sync() { __builtin_amdgcn_wave_barrier(); }
+
+// Operand and result layout of v_mfma_f32_32x32x2_f32 (A is 32x2, B is 2x32, D is 32x32):
+//   A: lane l holds A[l % 32][l / 32]
+//   B: lane l holds B[l / 32][l % 32]
+//   D: register v (0..15) of lane l holds D[8 * (v / 4) + 4 * (l / 32) + v % 4][l % 32]
+__device__ __forceinline__ int acc_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
+
+// acc[ti][tj] = sum_k X[i][k] * Y[k][j] over k < kdim (kdim even), tiles of 32x32.
+// XT / YT: the operand is stored transposed in its LDS buffer.
+template <int NT, bool XT, bool YT>
+__device__ __forceinline__ void product(floatx16 (&acc)[NT][NT], const float* X, const float* Y, int kdim, int lane) {
+    constexpr int LD = 32 * NT + 1;
+    const int lo = lane & 31, hi = lane >> 5;
+#pragma unroll
+    for (int ti = 0; ti < NT; ++ti)
+#pragma unroll
+        for (int tj = 0; tj < NT; ++tj)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[ti][tj][v] = 0.f;
+    for (int k0 = 0; k0 < kdim; k0 += 2) {
+        const int k = k0 + hi;
+        float a[NT], b[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int r = 32 * t + lo;
+            a[t] = XT ? X[k * LD + r] : X[r * LD + k];
+            b[t] = YT ? Y[r * LD + k] : Y[k * LD + r];
+        }
+#pragma unroll
+        for (int ti = 0; ti < NT; ++ti)
+#pragma unroll
+            for (int tj = 0; tj < NT; ++tj)
+                acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ti], b[tj], acc[ti][tj], 0, 0, 0);
+    }
+}
+
+template <int NT>
+__device__ __forceinline__ void spill_to_lds(const floatx16 (&acc)[NT][NT], float* dst, int lane) {
+    constexpr int LD = 32 * NT + 1;
+#pragma unroll
+    for (int ti = 0; ti < NT; ++ti)
+#pragma unroll
+        for (int tj = 0; tj < NT; ++tj)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                dst[(32 * ti + acc_row(v, lane)) * LD + 32 * tj + (lane & 31)] = acc[ti][tj][v];
+}
+
+// Coupling of the pair (a, b) = (lambda_i, lambda_j), i != j.
+__device__ __forceinline__ float coupling(float a, float b, bool j_later, int mode, int degree, float gap_floor) {
+    if (mode == kGradExact) {
+        const float d = b - a;
+        return (fabsf(d) >= gap_floor && d != 0.f) ? 1.0f / d : 0.f;
+    }
+    // truncated series: with b the larger in magnitude, 1/(b - a) ~ (1/b) sum_{k<=degree} (a/b)^k;
+    // mirrored otherwise.  Equal magnitudes: the later index counts as the larger, which keeps
+    // K antisymmetric.
+    const bool big_b = fabsf(b) > fabsf(a) || (fabsf(b) == fabsf(a) && j_later);
+    const float num = big_b ? a : b, den = big_b ? b : a;
+    if (den == 0.f) return 0.f;
+    const float rden = 1.0f / den;
+    const float rho = num * rden;
+    float s = 1.f;
+    for (int k = 0; k < degree; ++k) s = fmaf(s, rho, 1.f);
+    const float kk = s * rden;
+    return big_b ? kk : -kk;
+}
+
+// Divided difference of f~(x) = f(max(x, floor)) at (lambda_i, lambda_j); the derivative when they coincide.
+__device__ __forceinline__ float divided_difference(float li, float lj, int mode, float floor) {
+    const float ai = fmaxf(li, floor), aj = fmaxf(lj, floor);
+    const float si = sqrtf(ai), sj = sqrtf(aj);
+    // for unclamped arguments: (f(ai) - f(aj)) / (ai - aj) in a form without cancellation
+    float phi = (mode == kGradSqrt) ? 1.0f / (si + sj) : -1.0f / (si * sj * (si + sj));
+    if (li < floor || lj < floor) {
+        // f~(li) - f~(lj) = (f(ai) - f(aj)); the denominator is the distance of the true eigenvalues
+        phi = (ai == aj) ? 0.f : phi * ((ai - aj) / (li - lj));
+    }
+    return phi;
+}
+
+template <int NT>
+__global__ __launch_bounds__(64) void grad_kernel(GradArgs args) {
+    constexpr int NP = 32 * NT;
+    constexpr int LD = NP + 1;
+    __shared__ float sV[NP * LD];      // V, row-major, zero padded
+    __shared__ float sW[NP * LD];      // G, then the intermediate products
+    __shared__ float sL[NP];           // eigenvalues
+    __shared__ float sGl[NP];          // upstream gradient of the eigenvalues
+
+    const int lane = threadIdx.x;
+    const int b = blockIdx.x;
+    const int n = args.n;
+    const int kdim = (n + 1) & ~1;
+    const bool ed = (args.mode == kGradExact || args.mode == kGradTaylor);
+
+    for (int idx = lane; idx < NP * LD; idx += 64) {
+        sV[idx] = 0.f;
+        sW[idx] = 0.f;
+    }
+    if (lane < NP) {
+        sL[lane] = (lane < n) ? args.evals[(size_t)b * n + lane] : 0.f;
+        sGl[lane] = (lane < n && args.g_evals) ? args.g_evals[(size_t)b * n + lane] : 0.f;
+    }
+    wave_sync();
+    {
+        const float* __restrict__ Vb = args.evecs + (size_t)b * n * n;
+        const float* __restrict__ Gb = args.g_mat ? args.g_mat + (size_t)b * n * n : nullptr;
+        const float rcp_n = 1.0f / (float)n;
+        for (int idx = lane; idx < n * n; idx += 64) {
+            const int i = (int)(((float)idx + 0.5f) * rcp_n);
+            const int j = idx - i * n;
+            sV[i * LD + j] = Vb[idx];
+            if (Gb) sW[i * LD + j] = Gb[idx];
+        }
+    }
+    wave_sync();
+
+    floatx16 acc[NT][NT];
+    if (!ed) {
+        // spectral function: T = G V first, so that C = V^T G V
+        product<NT, false, false>(acc, sW, sV, kdim, lane);
+        wave_sync();
+        spill_to_lds<NT>(acc, sW, lane);
+        wave_sync();
+    }
+    // C = V^T T  (T = g_V for the eigendecomposition itself)
+    product<NT, true, false>(acc, sV, sW, kdim, lane);
+    wave_sync();
+    spill_to_lds<NT>(acc, sW, lane);
+    wave_sync();
+    // M: element (i, j) needs C_ij (own register), C_ji, lambda_i, lambda_j
+#pragma unroll
+    for (int ti = 0; ti < NT; ++ti)
+#pragma unroll
+        for (int tj = 0; tj < NT; ++tj)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int i = 32 * ti + acc_row(v, lane);
+                const int j = 32 * tj + (lane & 31);
+                const float cij = acc[ti][tj][v];
+                const float cji = sW[j * LD + i];
+                const float li = sL[i], lj = sL[j];
+                float m;
+                if (ed) {
+                    m = (i == j) ? sGl[i] : 0.5f * coupling(li, lj, j > i, args.mode, args.degree, args.param) * (cij - cji);
+                } else {
+                    m = 0.5f * divided_difference(li, lj, args.mode, args.param) * (cij + cji);
+                }
+                acc[ti][tj][v] = (i < n && j < n) ? m : 0.f;
+            }
+    wave_sync();
+    spill_to_lds<NT>(acc, sW, lane);
+    wave_sync();
+    // U = V M
+    product<NT, false, false>(acc, sV, sW, kdim, lane);
+    wave_sync();
+    spill_to_lds<NT>(acc, sW, lane);
+    wave_sync();
+    // g_A = U V^T
+    product<NT, false, true>(acc, sW, sV, kdim, lane);
+    float* __restrict__ Ob = args.g_A + (size_t)b * n * n;
+#pragma unroll
+    for (int ti = 0; ti < NT; ++ti)
+#pragma unroll
+        for (int tj = 0; tj < NT; ++tj)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int i = 32 * ti + acc_row(v, lane);
+                const int j = 32 * tj + (lane & 31);
+                if (i < n && j < n) Ob[i * n + j] = acc[ti][tj][v];
+            }
+}
+
+}  // namespace
+
+hipError_t launch_grad(const GradArgs& args, hipStream_t stream) {
+    if (args.batch == 0) return hipSuccess;
+    if (args.n <= 32)
+        hipLaunchKernelGGL(grad_kernel<1>, dim3(args.batch), dim3(64), 0, stream, args);
+    else
+        hipLaunchKernelGGL(grad_kernel<2>, dim3(args.batch), dim3(64), 0, stream, args);
+    return hipGetLastError();
+}
+
+}  // namespace bed

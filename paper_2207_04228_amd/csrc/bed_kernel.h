@@ -31,6 +31,24 @@ struct KernelArgs {
 #endif
 };
 
+// Gradient kernels (bed_grad.hip).
+enum GradMode { kGradExact = 0, kGradTaylor = 1, kGradSqrt = 2, kGradInvSqrt = 3 };
+
+struct GradArgs {
+    const float* evals;    // [batch][n]
+    const float* evecs;    // [batch][n][n], eigenvectors as columns
+    const float* g_evals;  // [batch][n] or nullptr        (kGradExact, kGradTaylor)
+    const float* g_mat;    // [batch][n][n] or nullptr: gradient w.r.t. evecs, or w.r.t. the spectral function
+    float* g_A;            // [batch][n][n]
+    int batch;
+    int n;
+    int mode;              // GradMode
+    int degree;            // kGradTaylor: degree of the truncated series
+    float param;           // kGradExact: gap floor; kGradSqrt / kGradInvSqrt: eigenvalue floor
+};
+
+hipError_t launch_grad(const GradArgs& args, hipStream_t stream);
+
 // Enqueue one launch; returns hipGetLastError() of the launch.
 hipError_t launch(const KernelArgs& args, int stage, int shift, bool want_v, hipStream_t stream);
 

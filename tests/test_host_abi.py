@@ -28,7 +28,7 @@ def _declared_symbols():
 
 def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
-    assert {"bed_syevd", "bed_syevd_info", "bed_tridiag", "bed_tridiag_qr", "bed_spd_fn",
+    assert {"bed_syevd", "bed_syevd_info", "bed_tridiag", "bed_tridiag_qr", "bed_spd_fn", "bed_syevd_backward", "bed_spd_fn_backward",
             "bed_status_string", "bed_version"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
@@ -69,6 +69,20 @@ def test_argument_validation_is_host_side(lib):
     assert lib.bed_spd_fn(A, 1, 65, 0, f(0.0), V, None, None, None) == -3
     assert lib.bed_spd_fn(A, 1, 4, 0, f(0.0), p(0x10020), None, None, None) == -6  # out overlaps A
     assert lib.bed_spd_fn(A, 0, 4, 0, f(0.0), V, None, None, None) == 0
+    O = p(0x50000)
+    assert lib.bed_syevd_backward(L, V, None, None, 1, 4, 0, 9, f(0.0), O, None) == -1      # no gradient given
+    assert lib.bed_syevd_backward(None, V, L, None, 1, 4, 0, 9, f(0.0), O, None) == -1
+    assert lib.bed_syevd_backward(L, V, L, None, 1, 4, 2, 9, f(0.0), O, None) == -7         # unknown mode
+    assert lib.bed_syevd_backward(L, V, L, None, 1, 4, 1, 65, f(0.0), O, None) == -7        # degree out of range
+    assert lib.bed_syevd_backward(L, V, L, None, 1, 4, 0, 9, f(float("nan")), O, None) == -7
+    assert lib.bed_syevd_backward(L, V, L, None, 1, 4, 0, 9, f(0.0), V, None) == -6         # output aliases evecs
+    assert lib.bed_syevd_backward(L, V, L, None, 1, 65, 0, 9, f(0.0), O, None) == -3
+    assert lib.bed_syevd_backward(L, V, L, None, 0, 4, 0, 9, f(0.0), O, None) == 0
+    assert lib.bed_spd_fn_backward(L, V, None, 1, 4, 0, f(0.0), O, None) == -1
+    assert lib.bed_spd_fn_backward(L, V, A, 1, 4, 1, f(0.0), O, None) == -7                 # inverse sqrt, floor 0
+    assert lib.bed_spd_fn_backward(L, V, A, 1, 4, 3, f(1.0), O, None) == -7
+    assert lib.bed_spd_fn_backward(L, V, A, 1, 4, 0, f(0.0), A, None) == -6
+    assert lib.bed_spd_fn_backward(L, V, A, 0, 4, 0, f(0.0), O, None) == 0
 
 
 def test_binding_rejects_cpu_tensors():

@@ -77,9 +77,11 @@ def test_taylor_coupling_is_the_truncated_geometric_series(degree):
     off = ~np.eye(7, dtype=bool)
     assert np.allclose(K[:, off], (Kx * (1 - r ** (degree + 1)))[:, off], rtol=1e-10)
     assert np.allclose(K, -np.swapaxes(K, 1, 2))
-    lam2 = np.array([[0.7, 0.7, 1.9]])
+    # equal eigenvalues: finite, (D+1)/lambda in magnitude, and still antisymmetric
+    lam2 = np.array([[0.7, 0.7, 0.7, 1.9]])
     K2 = backward.coupling_taylor(lam2, degree)
-    assert abs(K2[0, 0, 1]) == pytest.approx((degree + 1) / 0.7)
+    assert K2[0, 0, 1] == pytest.approx((degree + 1) / 0.7) and K2[0, 1, 2] == pytest.approx((degree + 1) / 0.7)
+    assert np.array_equal(K2, -np.swapaxes(K2, 1, 2))
 
 
 def test_taylor_gradient_converges_to_the_exact_one():
