@@ -43,6 +43,11 @@ def build(force: bool = False, remarks: bool = False, jobs: int = 8) -> str:
     sources = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
     headers = sorted(glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(CSRC, "*.hpp"))
                      + glob.glob(os.path.join(ROOT, "include", "*.h")))
+    # a change of compiler flags rebuilds everything
+    stamp = os.path.join(OBJ, "flags.txt")
+    flags_now = " ".join([HIPCC] + FLAGS)
+    if not os.path.exists(stamp) or open(stamp).read() != flags_now:
+        force = True
     objs = []
     todo = []
     for s in sources:
@@ -67,6 +72,8 @@ def build(force: bool = False, remarks: bool = False, jobs: int = 8) -> str:
     if todo:
         with cf.ThreadPoolExecutor(max_workers=max(1, min(jobs, len(todo)))) as ex:
             list(ex.map(compile_one, todo))
+    with open(stamp, "w") as f:
+        f.write(flags_now)
     if todo or force or not os.path.exists(LIB):
         cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
         r = subprocess.run(cmd, capture_output=True, text=True)

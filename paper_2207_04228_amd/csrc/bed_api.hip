@@ -23,7 +23,7 @@ int check_common(int batch, int n) {
 
 int run(const bed::KernelArgs& args, int stage, bool want_v, void* stream) {
     if (args.batch == 0) return BED_OK;
-    hipError_t err = bed::launch(args, stage, bed::kShiftDouble, want_v, static_cast<hipStream_t>(stream));
+    hipError_t err = bed::launch(args, stage, want_v, static_cast<hipStream_t>(stream));
     return err == hipSuccess ? BED_OK : BED_ERR_LAUNCH;
 }
 

@@ -4,15 +4,15 @@
 namespace bed {
 
 hipError_t launch_lane(const KernelArgs&, bool, hipStream_t);
-hipError_t launch_wave_n4(const KernelArgs&, int, int, bool, hipStream_t);
-hipError_t launch_wave_n8(const KernelArgs&, int, int, bool, hipStream_t);
-hipError_t launch_wave_n16(const KernelArgs&, int, int, bool, hipStream_t);
-hipError_t launch_wave_n24(const KernelArgs&, int, int, bool, hipStream_t);
-hipError_t launch_wave_n32(const KernelArgs&, int, int, bool, hipStream_t);
-hipError_t launch_wave_n48(const KernelArgs&, int, int, bool, hipStream_t);
-hipError_t launch_wave_n64(const KernelArgs&, int, int, bool, hipStream_t);
+hipError_t launch_wave_n4(const KernelArgs&, int, bool, hipStream_t);
+hipError_t launch_wave_n8(const KernelArgs&, int, bool, hipStream_t);
+hipError_t launch_wave_n16(const KernelArgs&, int, bool, hipStream_t);
+hipError_t launch_wave_n24(const KernelArgs&, int, bool, hipStream_t);
+hipError_t launch_wave_n32(const KernelArgs&, int, bool, hipStream_t);
+hipError_t launch_wave_n48(const KernelArgs&, int, bool, hipStream_t);
+hipError_t launch_wave_n64(const KernelArgs&, int, bool, hipStream_t);
 
-hipError_t launch(const KernelArgs& args, int stage, int shift, bool want_v, hipStream_t stream) {
+hipError_t launch(const KernelArgs& args, int stage, bool want_v, hipStream_t stream) {
     if (args.batch == 0) return hipSuccess;
     const int n = args.n;
     // Tiny matrices in very large batches: one matrix per lane (64 per wavefront).  Below these
@@ -20,13 +20,13 @@ hipError_t launch(const KernelArgs& args, int stage, int shift, bool want_v, hip
     // per-matrix latency is much lower, finish first (measured crossovers on MI355X).
     if (stage == kFull && ((n <= 4 && args.batch >= 8192) || (n <= 8 && args.batch >= 16384)))
         return launch_lane(args, want_v, stream);
-    if (n <= 4) return launch_wave_n4(args, stage, shift, want_v, stream);
-    if (n <= 8) return launch_wave_n8(args, stage, shift, want_v, stream);
-    if (n <= 16) return launch_wave_n16(args, stage, shift, want_v, stream);
-    if (n <= 24) return launch_wave_n24(args, stage, shift, want_v, stream);
-    if (n <= 32) return launch_wave_n32(args, stage, shift, want_v, stream);
-    if (n <= 48) return launch_wave_n48(args, stage, shift, want_v, stream);
-    return launch_wave_n64(args, stage, shift, want_v, stream);
+    if (n <= 4) return launch_wave_n4(args, stage, want_v, stream);
+    if (n <= 8) return launch_wave_n8(args, stage, want_v, stream);
+    if (n <= 16) return launch_wave_n16(args, stage, want_v, stream);
+    if (n <= 24) return launch_wave_n24(args, stage, want_v, stream);
+    if (n <= 32) return launch_wave_n32(args, stage, want_v, stream);
+    if (n <= 48) return launch_wave_n48(args, stage, want_v, stream);
+    return launch_wave_n64(args, stage, want_v, stream);
 }
 
 }  // namespace bed

@@ -9,7 +9,6 @@ namespace bed {
 
 enum Stage { kFull = 0, kTridiagOnly = 1, kQrOnly = 2, kSpectral = 3 };
 enum SpectralFn { kFnSqrt = 0, kFnInvSqrt = 1 };
-enum ShiftPolicy { kShiftDouble = 0, kShiftSingle = 1 };
 
 struct KernelArgs {
     const float* A;      // [batch][n][n]            (kFull, kTridiagOnly)
@@ -50,7 +49,7 @@ struct GradArgs {
 hipError_t launch_grad(const GradArgs& args, hipStream_t stream);
 
 // Enqueue one launch; returns hipGetLastError() of the launch.
-hipError_t launch(const KernelArgs& args, int stage, int shift, bool want_v, hipStream_t stream);
+hipError_t launch(const KernelArgs& args, int stage, bool want_v, hipStream_t stream);
 
 }  // namespace bed
 

@@ -240,13 +240,10 @@ __device__ __forceinline__ void chain_finish(const Chain& S, float& e_out, float
 // N      register-array size (4, 8, 16, 24, 32, 48, 64); n <= N at run time
 // WANT_V accumulate eigenvectors
 // STAGE  kFull, kTridiagOnly (stage hook 1), kQrOnly (stage hook 2)
-// SHIFT  kShiftDouble: both eigenvalues of the trailing 2x2 are taken once per
-//        outer iteration (Sec. 3.2.2); the second sweep uses the second one
-//        unless the first sweep already changed the active window.
-//        kShiftSingle: the eigenvalue closer to the last diagonal entry is
-//        recomputed before every sweep.
+// Shifts: both eigenvalues of the trailing 2x2 block of the active window are taken
+// once per outer iteration and used by two sweeps over the same window (Sec. 3.2.2).
 // ---------------------------------------------------------------------------
-template <int N, bool WANT_V, int STAGE, int SHIFT>
+template <int N, bool WANT_V, int STAGE>
 __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
     constexpr int W = lanes_for(N);
     // When the rows fit in half a wavefront (N <= 32), lanes 32..63 shadow rows 0..31 from
@@ -480,29 +477,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                 if (WANT_V) y_ = sV[((t_) + 3) * LD + vrow];    \
             } while (0)
 
-            if (SHIFT == kShiftSingle) {
-                // one sweep over the window [lo, hi]: rotations k = lo .. hi-1
-                float eo, dq, vo = 0.f;
-#define BED_STEP1(q_, y_, k_)                                           \
-                do {                                                    \
-                    chain_rotate<WANT_V>(A, q_.x, q_.y, y_, eo, dq, vo); \
-                    BED_REFILL(q_, y_, k_);                             \
-                    sP[k_] = make_float2(eo, dq);                       \
-                    if (WANT_V) sV[(k_) * LD + vrow] = vo;              \
-                } while (0)
-                int k = lo;
-                for (; k + 1 < hi; k += 2) {
-                    BED_STEP1(q0, y0, k);
-                    BED_STEP1(q1, y1, k + 1);
-                }
-                if (k < hi) BED_STEP1(q0, y0, k);
-#undef BED_STEP1
-                chain_finish(A, eo, dq, vo);
-                sP[hi] = make_float2(eo, dq);
-                if (WANT_V) sV[hi * LD + vrow] = vo;
-                rotations += (uint32_t)(hi - lo);
-                sweeps += 1;
-            } else {
+            {
                 // Two sweeps (shift mu1, then mu2) over the same window, software-pipelined:
                 // sweep B runs two rotations behind sweep A and takes A's results straight
                 // from registers.  At step t: B handles row t-2 with A's outputs of step t-1,
@@ -738,28 +713,25 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
 // ---------------------------------------------------------------------------
 // host-side dispatch for one register-array size
 // ---------------------------------------------------------------------------
-template <int N, bool WANT_V, int STAGE, int SHIFT>
+template <int N, bool WANT_V, int STAGE>
 static hipError_t launch_one(const KernelArgs& args, hipStream_t stream) {
-    hipLaunchKernelGGL((wave_kernel<N, WANT_V, STAGE, SHIFT>), dim3(args.batch), dim3(64), 0, stream, args);
+    hipLaunchKernelGGL((wave_kernel<N, WANT_V, STAGE>), dim3(args.batch), dim3(64), 0, stream, args);
     return hipGetLastError();
 }
 
 template <int N>
-static hipError_t launch_n(const KernelArgs& args, int stage, int shift, bool want_v, hipStream_t stream) {
-    // Only the paper's double shift is instantiated; kShiftSingle stays in the source
-    // as the reference single-sweep loop for experiments.
-    (void)shift;
+static hipError_t launch_n(const KernelArgs& args, int stage, bool want_v, hipStream_t stream) {
     if (stage == kTridiagOnly) {
-        return want_v ? launch_one<N, true, kTridiagOnly, kShiftDouble>(args, stream)
-                      : launch_one<N, false, kTridiagOnly, kShiftDouble>(args, stream);
+        return want_v ? launch_one<N, true, kTridiagOnly>(args, stream)
+                      : launch_one<N, false, kTridiagOnly>(args, stream);
     }
     if (stage == kQrOnly) {
-        return want_v ? launch_one<N, true, kQrOnly, kShiftDouble>(args, stream)
-                      : launch_one<N, false, kQrOnly, kShiftDouble>(args, stream);
+        return want_v ? launch_one<N, true, kQrOnly>(args, stream)
+                      : launch_one<N, false, kQrOnly>(args, stream);
     }
-    if (stage == kSpectral) return launch_one<N, true, kSpectral, kShiftDouble>(args, stream);
-    return want_v ? launch_one<N, true, kFull, kShiftDouble>(args, stream)
-                  : launch_one<N, false, kFull, kShiftDouble>(args, stream);
+    if (stage == kSpectral) return launch_one<N, true, kSpectral>(args, stream);
+    return want_v ? launch_one<N, true, kFull>(args, stream)
+                  : launch_one<N, false, kFull>(args, stream);
 }
 
 }  // namespace bed

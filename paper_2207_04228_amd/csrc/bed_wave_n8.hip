@@ -2,7 +2,7 @@
 #include "bed_wave_kernel.hpp"
 
 namespace bed {
-hipError_t launch_wave_n8(const KernelArgs& args, int stage, int shift, bool want_v, hipStream_t stream) {
-    return launch_n<8>(args, stage, shift, want_v, stream);
+hipError_t launch_wave_n8(const KernelArgs& args, int stage, bool want_v, hipStream_t stream) {
+    return launch_n<8>(args, stage, want_v, stream);
 }
 }  // namespace bed
