@@ -64,11 +64,20 @@ __device__ __forceinline__ float read_lane(float x, int lane_uniform) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), lane_uniform));
 }
 
-// Every lane receives the value held by lane (i & 31), i.e. the lower half's values are
-// copied over the upper half (v_permlane32_swap of a register with a copy of itself).
-__device__ __forceinline__ float from_lower_half(float x) {
-    const unsigned u = __float_as_uint(x);
-    return __uint_as_float(__builtin_amdgcn_permlane32_swap(u, u, false, false)[0]);
+// Lanes 0..31 keep `keep`; lane 32 + i receives the value lane i holds in `src`
+// (v_permlane32_swap exchanges the upper half of its first operand with the lower half of
+// its second; the first result is the first operand after the exchange).
+__device__ __forceinline__ float upper_from_lower(float keep, float src) {
+    return __uint_as_float(
+        __builtin_amdgcn_permlane32_swap(__float_as_uint(keep), __float_as_uint(src), false, false)[0]);
+}
+
+// Lanes 0..31 keep `keep`; lanes 32..63 receive the value lane 31 holds in `src`
+// (DPP row_bcast31 restricted to rows 2 and 3): one instruction hands a value that is
+// uniform over the lower half to the upper half.
+__device__ __forceinline__ float upper_from_lane31(float keep, float src) {
+    return __int_as_float(
+        __builtin_amdgcn_update_dpp(__float_as_int(keep), __float_as_int(src), kRowBcast31, 0xC, 0xF, false));
 }
 
 // Sum over lanes [0, W) of the wave (W = 8, 16, 32 or 64, lanes outside must
@@ -505,8 +514,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                     // Role lanes: lanes 0..31 carry sweep A, lanes 32..63 carry sweep B, so one
                     // instruction stream advances both sweeps by one rotation per step.
                     // B's inputs are A's outputs of the previous step, copied from the lower
-                    // half of the wavefront.  Only B's results are stored; A lanes store to a
-                    // dump slot.
+                    // half of the wavefront.
                     const float sD = pD, sX = pV;              // d'[lo], column lo as left by A
                     // t = lo + 1: A rotates row lo+1 (still computed by every lane)
                     chain_rotate<WANT_V>(A, q1.x, q1.y, y1, pE, pD, pV);
@@ -519,10 +527,10 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                     S.p = roleB ? 0.f : A.p;
                     S.dk = roleB ? sD : A.dk;
                     S.x = roleB ? sX : A.x;
-                    // B's inputs: A's outputs of the previous step.  e and d are uniform over the A
-                    // lanes and travel through a scalar register; the V entry is per row and is
-                    // copied from the lower half.
-                    float inE = pE, inD = pD, inV = pV;
+                    // B's inputs are A's outputs of the previous step.  e and d are uniform over the
+                    // A lanes: one DPP broadcast of lane 31 into the upper half merges them with the A
+                    // lanes' own inputs.  The V entry is per row: a half swap does the same merge.
+                    float prevE = pE, prevD = pD, prevV = pV;
                     // One running LDS pointer per lane and array; every lane stores at the pointer
                     // and loads three positions above it.  A lanes: the pointer is at position t,
                     // so the load fetches the inputs of rotation t+2 (position t+3) and the store
@@ -535,17 +543,17 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                     float oE, oD, oV = 0.f;
 #define BED_STEPH(q_, y_, k_)                                                       \
                     do {                                                            \
-                        const float e_in = roleB ? inE : q_.x;                      \
-                        const float d_in = roleB ? inD : q_.y;                      \
-                        const float y_in = roleB ? inV : y_;                        \
+                        const float e_in = upper_from_lane31(q_.x, prevE);          \
+                        const float d_in = upper_from_lane31(q_.y, prevD);          \
+                        const float y_in = WANT_V ? upper_from_lower(y_, prevV) : 0.f; \
                         chain_rotate<WANT_V>(S, e_in, d_in, y_in, oE, oD, oV);      \
                         q_ = xP[(k_) + AHEAD];                                      \
                         if (WANT_V) y_ = xV[((k_) + AHEAD) * LD];                   \
                         const_cast<float2*>(xP)[(k_)] = make_float2(oE, oD);        \
                         if (WANT_V) const_cast<float*>(xV)[(k_) * LD] = oV;         \
-                        inE = read_lane(oE, 0);                                     \
-                        inD = read_lane(oD, 0);                                     \
-                        if (WANT_V) inV = from_lower_half(oV);                      \
+                        prevE = oE;                                                 \
+                        prevD = oD;                                                 \
+                        prevV = oV;                                                 \
                     } while (0)
                     int t = lo + 2;
                     for (; t + 1 < hi; t += 2) {
@@ -568,14 +576,13 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                     // t = hi: A closes (values taken before its state is overwritten); B rotates row hi-2
                     float fE, fD, fV;
                     chain_finish(S, fE, fD, fV);
-                    chain_rotate<WANT_V>(S, inE, inD, inV, oE, oD, oV);
+                    chain_rotate<WANT_V>(S, upper_from_lane31(prevE, prevE), upper_from_lane31(prevD, prevD),
+                                         WANT_V ? upper_from_lower(prevV, prevV) : 0.f, oE, oD, oV);
                     const_cast<float2*>(xP)[0] = make_float2(oE, oD);
                     if (WANT_V) const_cast<float*>(xV)[0] = oV;
                     // t = hi + 1: B rotates row hi-1 with A's closing values
-                    inE = read_lane(fE, 0);
-                    inD = read_lane(fD, 0);
-                    if (WANT_V) inV = from_lower_half(fV);
-                    chain_rotate<WANT_V>(S, inE, inD, inV, oE, oD, oV);
+                    chain_rotate<WANT_V>(S, upper_from_lane31(fE, fE), upper_from_lane31(fD, fD),
+                                         WANT_V ? upper_from_lower(fV, fV) : 0.f, oE, oD, oV);
                     const_cast<float2*>(xP)[1] = make_float2(oE, oD);
                     if (WANT_V) const_cast<float*>(xV)[LD] = oV;
                     // t = hi + 2: B closes
