@@ -182,60 +182,6 @@ __device__ __forceinline__ void chain_rotate(Chain& S, float ek, float dk1, floa
     S.dk = dk1;
 }
 
-// Two independent rotations (one per sweep) written statement by statement in
-// alternation, so that the in-order instruction stream always has an
-// independent instruction to issue behind a dependent one.
-template <bool WANT_V>
-__device__ __forceinline__ void chain_rotate2(Chain& A, float ekA, float dk1A, float yA,
-                                              float& eA, float& dA, float& vA,
-                                              Chain& B, float ekB, float dk1B, float yB,
-                                              float& eB, float& dB, float& vB) {
-    const float g0A = guard_g(A.g);
-    const float g0B = guard_g(B.g);
-    const float fA = A.s * ekA;
-    const float fB = B.s * ekB;
-    const float ggA = g0A * g0A;
-    const float ggB = g0B * g0B;
-    const float bA = A.c * ekA;
-    const float bB = B.c * ekB;
-    const float hA = fmaf(fA, fA, ggA);
-    const float hB = fmaf(fB, fB, ggB);
-    const float gA = A.dk - A.p;
-    const float gB = B.dk - B.p;
-    const float riA = __builtin_amdgcn_rsqf(hA);
-    const float riB = __builtin_amdgcn_rsqf(hB);
-    const float tA = dk1A - gA;
-    const float tB = dk1B - gB;
-    A.c = g0A * riA;
-    B.c = g0B * riB;
-    A.s = fA * riA;
-    B.s = fB * riB;
-    const float cbA = 2.f * A.c * bA;
-    const float cbB = 2.f * B.c * bB;
-    const float r2A = fmaf(tA, A.s, cbA);
-    const float r2B = fmaf(tB, B.s, cbB);
-    eA = hA * riA;
-    eB = hB * riB;
-    A.p = A.s * r2A;
-    B.p = B.s * r2B;
-    A.g = fmaf(A.c, r2A, -bA);
-    B.g = fmaf(B.c, r2B, -bB);
-    dA = gA + A.p;
-    dB = gB + B.p;
-    if (WANT_V) {
-        const float syA = A.s * yA;
-        const float syB = B.s * yB;
-        const float sxA = A.s * A.x;
-        const float sxB = B.s * B.x;
-        vA = fmaf(A.c, A.x, syA);
-        vB = fmaf(B.c, B.x, syB);
-        A.x = fmaf(A.c, yA, -sxA);
-        B.x = fmaf(B.c, yB, -sxB);
-    }
-    A.dk = dk1A;
-    B.dk = dk1B;
-}
-
 // end of a sweep at row hi: e[hi-1] = g, d[hi] -= p, column hi = carried column
 __device__ __forceinline__ void chain_finish(const Chain& S, float& e_out, float& d_out, float& v_out) {
     e_out = S.g;
@@ -593,48 +539,93 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                     sweeps += 2;
                     BED_PROBE(5);
                 } else {
-                    // Rows need the whole wavefront: both chains are computed by every lane,
-                    // interleaved statement by statement.
-                    // B starts from d'[lo] and column lo as left by A
-                    Chain B;
-                    chain_start<WANT_V>(B, pD, mu2, pV);
-                    // t = lo + 1: A rotates row lo+1
+                    // Rows need the whole wavefront.  The scalar recurrences of the two sweeps
+                    // still run in the two halves (lanes 0..31 sweep A, lanes 32..63 sweep B, two
+                    // rotations behind), but every lane owns a row of V: the rotation coefficients
+                    // of both sweeps are broadcast with v_readlane and every lane applies both
+                    // rotations to its row.
+                    const float sD = pD;                       // d'[lo] as left by A
+                    float xB = pV;                             // column lo as left by A: B's carried column
+                    // t = lo + 1: A rotates row lo+1 (still computed by every lane)
                     chain_rotate<WANT_V>(A, q1.x, q1.y, y1, pE, pD, pV);
                     BED_REFILL(q1, y1, lo + 1);
                     BED_PROBE(3);
-                    float eo, dq, vo = 0.f;     // B's outputs
-#define BED_STEP2(q_, y_, t_)                                                                    \
-                    do {                                                                         \
-                        float nE, nD, nV = 0.f;                                                  \
-                        chain_rotate2<WANT_V>(A, q_.x, q_.y, y_, nE, nD, nV, B, pE, pD, pV, eo, dq, vo); \
-                        BED_REFILL(q_, y_, t_);                                                  \
-                        sP[(t_) - 2] = make_float2(eo, dq);                                      \
-                        if (WANT_V) sV[((t_) - 2) * LD + vrow] = vo;                             \
-                        pE = nE;                                                                 \
-                        pD = nD;                                                                 \
-                        pV = nV;                                                                 \
+                    Chain S;                                   // this lane's recurrence: A or B (no V part)
+                    S.g = roleB ? (sD - mu2) : A.g;
+                    S.s = roleB ? 1.f : A.s;
+                    S.c = roleB ? 1.f : A.c;
+                    S.p = roleB ? 0.f : A.p;
+                    S.dk = roleB ? sD : A.dk;
+                    S.x = 0.f;
+                    float xA = A.x;                            // A's carried column
+                    float prevE = pE, prevD = pD;              // A's (e, d) of the previous step; pV is its column
+                    // T: one running pointer per lane as in the half-wavefront loop (store at the
+                    // pointer, load three positions above).  V: every lane stores column t-2 and
+                    // prefetches column t+3 of its own row.
+                    constexpr int AHEAD = 3;
+                    const float2* xP = sP + (roleB ? lo : (lo + 2));
+                    float* xVp = sV + lo * LD + vrow;
+                    float oE, oD, unused;
+#define BED_STEPW(q_, y_, k_)                                                       \
+                    do {                                                            \
+                        const float e_in = upper_from_lane31(q_.x, prevE);          \
+                        const float d_in = upper_from_lane31(q_.y, prevD);          \
+                        chain_rotate<false>(S, e_in, d_in, 0.f, oE, oD, unused);    \
+                        if (WANT_V) {                                               \
+                            const float cA = read_lane(S.c, 0), sA = read_lane(S.s, 0);   \
+                            const float cB = read_lane(S.c, 32), sB = read_lane(S.s, 32); \
+                            const float nV = fmaf(cA, xA, sA * y_);                 \
+                            xA = fmaf(cA, y_, -sA * xA);                            \
+                            const float vo = fmaf(cB, xB, sB * pV);                 \
+                            xB = fmaf(cB, pV, -sB * xB);                            \
+                            pV = nV;                                                \
+                            xVp[(k_) * LD] = vo;                                    \
+                            y_ = xVp[((k_) + 5) * LD];                              \
+                        }                                                           \
+                        q_ = xP[(k_) + AHEAD];                                      \
+                        const_cast<float2*>(xP)[(k_)] = make_float2(oE, oD);        \
+                        prevE = oE;                                                 \
+                        prevD = oD;                                                 \
                     } while (0)
                     int t = lo + 2;
                     for (; t + 1 < hi; t += 2) {
-                        // steady state: A rotates row t, B rotates row t-2
-                        BED_STEP2(q0, y0, t);
-                        BED_STEP2(q1, y1, t + 1);
+                        BED_STEPW(q0, y0, 0);
+                        BED_STEPW(q1, y1, 1);
+                        xVp += 2 * LD;
+                        xP += 2;
                     }
-                    if (t < hi) BED_STEP2(q0, y0, t);
-#undef BED_STEP2
+                    if (t < hi) {
+                        BED_STEPW(q0, y0, 0);
+                        xVp += LD;
+                        xP += 1;
+                    }
+#undef BED_STEPW
                     BED_PROBE(4);
-                    // t = hi: B rotates row hi-2 with A's outputs of row hi-1; A finishes
-                    chain_rotate<WANT_V>(B, pE, pD, pV, eo, dq, vo);
-                    sP[hi - 2] = make_float2(eo, dq);
-                    if (WANT_V) sV[(hi - 2) * LD + vrow] = vo;
-                    chain_finish(A, pE, pD, pV);
-                    // t = hi + 1: B rotates row hi-1 with A's closing values; t = hi + 2: B finishes
-                    chain_rotate<WANT_V>(B, pE, pD, pV, eo, dq, vo);
-                    sP[hi - 1] = make_float2(eo, dq);
-                    if (WANT_V) sV[(hi - 1) * LD + vrow] = vo;
-                    chain_finish(B, eo, dq, vo);
-                    sP[hi] = make_float2(eo, dq);
-                    if (WANT_V) sV[hi * LD + vrow] = vo;
+                    // closing steps: B alone; the A lanes' T stores are parked in the padding
+                    xP = roleB ? xP : (sP + (N + 3));
+                    float fE, fD, fx;
+                    chain_finish(S, fE, fD, fx);               // A lanes: e[hi-1], d[hi] as left by A
+                    // t = hi: B rotates row hi-2 with A's outputs of row hi-1
+                    chain_rotate<false>(S, upper_from_lane31(prevE, prevE), upper_from_lane31(prevD, prevD), 0.f,
+                                        oE, oD, unused);
+                    const_cast<float2*>(xP)[0] = make_float2(oE, oD);
+                    if (WANT_V) {
+                        const float cB = read_lane(S.c, 32), sB = read_lane(S.s, 32);
+                        xVp[0] = fmaf(cB, xB, sB * pV);
+                        xB = fmaf(cB, pV, -sB * xB);
+                    }
+                    // t = hi + 1: B rotates row hi-1 with A's closing values (column hi as left by A is xA)
+                    chain_rotate<false>(S, upper_from_lane31(fE, fE), upper_from_lane31(fD, fD), 0.f, oE, oD, unused);
+                    const_cast<float2*>(xP)[1] = make_float2(oE, oD);
+                    if (WANT_V) {
+                        const float cB = read_lane(S.c, 32), sB = read_lane(S.s, 32);
+                        xVp[LD] = fmaf(cB, xB, sB * xA);
+                        xB = fmaf(cB, xA, -sB * xB);
+                    }
+                    // t = hi + 2: B closes
+                    chain_finish(S, fE, fD, fx);
+                    const_cast<float2*>(xP)[2] = make_float2(fE, fD);
+                    if (WANT_V) xVp[2 * LD] = xB;
                     rotations += 2u * (uint32_t)(hi - lo);
                     sweeps += 2;
                     BED_PROBE(5);
