@@ -72,6 +72,13 @@ __device__ __forceinline__ float upper_from_lower(float keep, float src) {
         __builtin_amdgcn_permlane32_swap(__float_as_uint(keep), __float_as_uint(src), false, false)[0]);
 }
 
+// Every lane receives the value lane 32 + (i & 31) holds: the second result of the same
+// exchange applied to two copies of x is x with its upper half copied over its lower half.
+__device__ __forceinline__ float from_upper_half(float x) {
+    const unsigned u = __float_as_uint(x);
+    return __uint_as_float(__builtin_amdgcn_permlane32_swap(u, u, false, false)[1]);
+}
+
 // Lanes 0..31 keep `keep`; lanes 32..63 receive the value lane 31 holds in `src`
 // (DPP row_bcast31 restricted to rows 2 and 3): one instruction hands a value that is
 // uniform over the lower half to the upper half.
@@ -226,7 +233,87 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
 
     float inv_scale = 1.f;
 
-    if (STAGE != kQrOnly) {
+    if (STAGE != kQrOnly && HALF && WANT_V) {
+        // ---- rows fit in half a wavefront and P is wanted: the lower half holds the rows of
+        // the working matrix, the upper half the rows of the accumulated reflector product
+        // P (Eq. (8)).  One instruction stream serves both: the dot product with u gives
+        // p = 2Au/|u|^2 in the lower half and w = 2Pu/|u|^2 in the upper half, and the update
+        // x <- x - q u^T is the first half of the rank-2 update of A (q = p - K u) and the whole
+        // rank-1 update of P (q = w); the second half, x <- x - u q^T, runs with u = 0 in the
+        // upper half.
+        const bool roleP = lane >= 32;
+        const int arow = roleP ? -1 : row;         // row index for the selections on A; none for the P lanes
+        float x[N];
+        const float* __restrict__ Ab = args.A + (size_t)b * n * n;
+        const float rcp_n = 1.0f / (float)n;
+        for (int idx = lane; idx < n * n; idx += 64) {
+            int i = (int)(((float)idx + 0.5f) * rcp_n);
+            int j = idx - i * n;
+            sV[i * LD + j] = Ab[idx];
+        }
+        wave_sync();
+        float amax = 0.f;
+#pragma unroll
+        for (int c = 0; c < N; ++c) {
+            float aval = 0.f;
+            if (row < n && c < n) aval = (c <= row) ? sV[row * LD + c] : sV[c * LD + row];
+            amax = fmaxf(amax, fabsf(aval));   // fmaxf drops NaNs; they still reach the output through the arithmetic
+            x[c] = roleP ? ((c == row) ? 1.f : 0.f) : aval;
+        }
+        wave_sync();
+        float scale;
+        pow2_scale(wave_max_nonneg<W>(amax), scale, inv_scale);
+        const float myscale = roleP ? 1.f : scale;
+#pragma unroll
+        for (int c = 0; c < N; ++c) x[c] *= myscale;
+#pragma unroll
+        for (int J = 0; J < N; ++J) {
+            const float dJ = read_lane(x[J], J);      // final once columns 0..J-1 are reduced
+            float eJ = 0.f;
+            if (J < N - 1) {
+                const float x0 = read_lane(x[J], J + 1);     // A[J+1][J]
+                eJ = x0;                                      // kept as is when no reflector is applied
+                if (J < N - 2) {
+                    const float xc = (arow > J) ? x[J] : 0.f; // A[r][J], r > J
+                    const float alpha = wave_sum<W>(xc * xc); // |x|^2 (the sum reads the lower half only)
+                    const bool active = (J < n - 2) && (alpha > kTinyAlpha);
+                    const float nrm = __builtin_amdgcn_sqrtf(alpha);
+                    const float sigma = (x0 < 0.f) ? -nrm : nrm;   // sign chosen to avoid cancellation
+                    float ur = (arow == J + 1) ? (x0 + sigma) : ((arow > J + 1) ? xc : 0.f);
+                    ur = active ? ur : 0.f;
+                    const float beta = active ? __builtin_amdgcn_rcpf(fmaf(fabsf(x0), nrm, alpha)) : 0.f;  // 2/|u|^2
+                    eJ = active ? -sigma : x0;
+                    svec[lane] = ur;                          // entries 32..63 (P lanes) are zero and never read
+                    __syncthreads();
+                    float u[N];
+#pragma unroll
+                    for (int c = J + 1; c < N; ++c) u[c] = svec[c];
+                    float pp[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int c = J + 1; c < N; ++c) pp[c & 3] = fmaf(x[c], u[c], pp[c & 3]);
+                    const float pw = beta * ((pp[0] + pp[1]) + (pp[2] + pp[3]));     // p (A lanes), w (P lanes)
+                    const float K = 0.5f * beta * wave_sum<W>(ur * pw);
+                    const float q = fmaf(-K, ur, pw);         // q = p - K u; stays w in the P lanes (u = 0 there)
+                    sq[lane] = q;
+#pragma unroll
+                    for (int c = J + 1; c < N; ++c) x[c] = fmaf(-q, u[c], x[c]);
+                    __syncthreads();
+#pragma unroll
+                    for (int c = J + 1; c < N; ++c) x[c] = fmaf(-ur, sq[c], x[c]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            if (lane == 0) {
+                sP[J].y = dJ;
+                sP[J + 1].x = (J < n - 1) ? eJ : 0.f;
+            }
+        }
+        if (lane == 0) sP[0].x = 0.f;
+        // every lane stores the P lanes' row (the upper half's value copied over the lower half)
+#pragma unroll
+        for (int c = 0; c < N; ++c) sV[c * LD + row] = from_upper_half(x[c]);
+        wave_sync();
+    } else if (STAGE != kQrOnly) {
         float a[N];
         float v[N];
 #pragma unroll
