@@ -3,8 +3,9 @@
 // One wavefront owns one matrix from load to store.  The whole path of
 // arXiv 2207.04228 Sec. 3 runs inside one launch:
 //   Sec. 3.1   Householder tridiagonalisation (rank-2 update form, Eqs. (5)-(6));
-//              lane r holds row r of the working matrix and row r of the
-//              accumulated reflector product P (Eq. (8)) in VGPRs
+//              the rows of the working matrix and of the accumulated reflector
+//              product P (Eq. (8)) live in VGPRs, one row per lane (for n <= 32:
+//              A in lanes 0..31, P in lanes 32..63)
 //   Sec. 3.2   QR iterations by Givens rotations (App. A.1) with the two
 //              Wilkinson shifts of the trailing 2x2 block (Sec. 3.2.2, App. A.3),
 //              per-matrix deflation (Sec. 3.2.3), O(1) update of the
