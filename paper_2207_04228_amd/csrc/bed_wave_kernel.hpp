@@ -200,6 +200,320 @@ __device__ __forceinline__ void chain_finish(const Chain& S, float& e_out, float
 }  // namespace
 
 // ---------------------------------------------------------------------------
+// Shifted QR iterations (Sec. 3.2) on the tridiagonal in sP, rotating the columns of V in
+// sV, until every off-diagonal has deflated or the sweep cap is reached.  Runs in ONE
+// wavefront; `vrow` is the row of V this lane owns.
+//   HALF   the wavefront's rows of V fit in 32 lanes (lanes 32..63 shadow them): the two
+//          sweeps of an iteration run in the two halves, each lane rotating its row for
+//          its own sweep.  Otherwise every lane owns a row and rotates it for both sweeps.
+// On return d_lane[bank] holds d[lane + 64 * bank].
+// ---------------------------------------------------------------------------
+template <int N, bool HALF, bool WANT_V, int LD>
+__device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV, const int lane, const int vrow,
+                                              const int n, uint32_t& rotations, int& info,
+                                              float (&d_lane)[(N + 63) / 64], const KernelArgs& args, const int b) {
+    const bool roleB = lane >= 32;
+    const uint32_t cap = 30u * (uint32_t)n;
+    uint32_t sweeps = 0;
+    // Off-diagonal k = lane + 64 * bank is watched by this lane: e[k] not yet deflated.
+    constexpr int NB = (N + 63) / 64;
+    bool live[NB];
+    float dl[NB];
+#pragma unroll
+    for (int bk = 0; bk < NB; ++bk) {
+        live[bk] = lane + 64 * bk < n - 1;
+        dl[bk] = 0.f;
+    }
+    uint64_t nz[NB];
+    BED_PROBE_INIT();
+    while (true) {
+        BED_PROBE(0);
+        // deflation test, lane-parallel: the lane looks at e[k], d[k], d[k+1]
+        float el[NB], dnext[NB];
+        uint64_t any = 0;
+#pragma unroll
+        for (int bk = 0; bk < NB; ++bk) {
+            const int k = lane + 64 * bk;
+            el[bk] = 0.f;
+            dnext[bk] = 0.f;
+            if (k < N) {
+                const float2 pk = sP[k];
+                const float2 pk1 = sP[k + 1];
+                dl[bk] = pk.y;
+                el[bk] = pk1.x;
+                dnext[bk] = pk1.y;
+            }
+            live[bk] = live[bk] && !(fabsf(el[bk]) <= fmaxf(kEps * (fabsf(dl[bk]) + fabsf(dnext[bk])), kTinyE));
+            nz[bk] = __ballot(live[bk]);
+            any |= nz[bk];
+        }
+        if (any == 0 || sweeps >= cap) break;
+        // active window [lo, hi]: e[hi-1] is the last live entry, e[lo-1] the last dead one below it
+        int hi, lo;
+        if (NB == 2 && nz[NB - 1] != 0) {
+            hi = 128 - __builtin_clzll(nz[NB - 1]);
+            const uint64_t below1 = ~nz[NB - 1] & ((1ull << (hi - 65)) - 1ull);
+            const uint64_t below0 = ~nz[0];
+            lo = below1 ? 128 - __builtin_clzll(below1) : (below0 ? 64 - __builtin_clzll(below0) : 0);
+        } else {
+            hi = 64 - __builtin_clzll(nz[0]);
+            const uint64_t below = ~nz[0] & ((1ull << (hi - 1)) - 1ull);
+            lo = below ? 64 - __builtin_clzll(below) : 0;
+        }
+        // value of a lane-distributed entry at a wave-uniform index
+        auto at = [&](const float (&v)[NB], int idx) -> float {
+            return (NB == 1 || idx < 64) ? read_lane(v[0], idx & 63) : read_lane(v[NB - 1], idx - 64);
+        };
+
+        BED_PROBE(1);
+        // eigenvalues of the trailing block [[ta, tb], [tb, td]] (App. A.3), smaller-angle root first
+        const float ta = at(dl, hi - 1);
+        const float tb = at(el, hi - 1);
+        const float td = at(dnext, hi - 1);
+        const float delta = 0.5f * (ta - td);
+        const float rt = __builtin_amdgcn_sqrtf(fmaf(delta, delta, tb * tb));
+        const float den = delta + ((delta >= 0.f) ? rt : -rt);
+        const float tt = (tb * tb) * __builtin_amdgcn_rcpf(den);
+        const float mu1 = td - tt;          // eigenvalue closer to the last diagonal entry
+        const float mu2 = ta + tt;          // the other eigenvalue of the block
+
+        // Inputs of rotation t: (e[t], d[t+1]) = sP[t+1] and column t+1 of V.  They are
+        // fetched two rotations ahead into two slots used in alternation (slot 0: rotations
+        // lo, lo+2, ...; slot 1: rotations lo+1, lo+3, ...), so a slot is refilled right after
+        // it has been consumed and no register shuffling is needed.
+        const float d_lo = at(dl, lo);
+        float2 q0 = make_float2(at(el, lo), at(dnext, lo));
+        float2 q1 = sP[lo + 2];
+        float y0 = 0.f, y1 = 0.f;
+        Chain A;
+        chain_start<WANT_V>(A, d_lo, mu1, WANT_V ? sV[lo * LD + vrow] : 0.f);
+        if (WANT_V) {
+            y0 = sV[(lo + 1) * LD + vrow];
+            y1 = sV[(lo + 2) * LD + vrow];
+        }
+        // refill a slot with the inputs of rotation t_+2 (indices stay inside the padding)
+#define BED_REFILL(q_, y_, t_)                                  \
+        do {                                                \
+            q_ = sP[(t_) + 3];                              \
+            if (WANT_V) y_ = sV[((t_) + 3) * LD + vrow];    \
+        } while (0)
+
+        {
+            // Two sweeps (shift mu1, then mu2) over the same window, software-pipelined:
+            // sweep B runs two rotations behind sweep A and takes A's results straight
+            // from registers.  At step t: B handles row t-2 with A's outputs of step t-1,
+            // while A handles row t.
+            float pE, pD, pV = 0.f;     // A's outputs of the previous step
+            BED_PROBE(2);
+            // t = lo: A rotates row lo
+            chain_rotate<WANT_V>(A, q0.x, q0.y, y0, pE, pD, pV);
+            BED_REFILL(q0, y0, lo);
+            if (hi - lo == 1) {
+                // The window is the 2x2 block the shifts were taken from: the step with
+                // its exact eigenvalue mu1 diagonalises it (this is the rotation of
+                // App. A.3), so the off-diagonal is set to zero and no second sweep runs.
+                // (A second sweep here would start from (d'[lo] - mu2, e'[lo]) = rounding
+                // noise and could rotate the converged block by an arbitrary angle.)
+                sP[lo] = make_float2(pE, pD);
+                if (WANT_V) sV[lo * LD + vrow] = pV;
+                chain_finish(A, pE, pD, pV);
+                sP[hi] = make_float2(0.f, pD);
+                if (WANT_V) sV[hi * LD + vrow] = pV;
+                rotations += 1u;
+                sweeps += 1;
+                BED_PROBE(5);
+            } else if (HALF) {
+                // Role lanes: lanes 0..31 carry sweep A, lanes 32..63 carry sweep B, so one
+                // instruction stream advances both sweeps by one rotation per step.
+                // B's inputs are A's outputs of the previous step, copied from the lower
+                // half of the wavefront.
+                const float sD = pD, sX = pV;              // d'[lo], column lo as left by A
+                // t = lo + 1: A rotates row lo+1 (still computed by every lane)
+                chain_rotate<WANT_V>(A, q1.x, q1.y, y1, pE, pD, pV);
+                BED_REFILL(q1, y1, lo + 1);
+                BED_PROBE(3);
+                Chain S;                                   // this lane's chain: A or B
+                S.g = roleB ? (sD - mu2) : A.g;
+                S.s = roleB ? 1.f : A.s;
+                S.c = roleB ? 1.f : A.c;
+                S.p = roleB ? 0.f : A.p;
+                S.dk = roleB ? sD : A.dk;
+                S.x = roleB ? sX : A.x;
+                // B's inputs are A's outputs of the previous step.  e and d are uniform over the
+                // A lanes: one DPP broadcast of lane 31 into the upper half merges them with the A
+                // lanes' own inputs.  The V entry is per row: a half swap does the same merge.
+                float prevE = pE, prevD = pD, prevV = pV;
+                // One running LDS pointer per lane and array; every lane stores at the pointer
+                // and loads three positions above it.  A lanes: the pointer is at position t,
+                // so the load fetches the inputs of rotation t+2 (position t+3) and the store
+                // lands on a position A has already consumed and B overwrites with the final
+                // value two steps later.  B lanes: the pointer is at position t-2, so the
+                // store is the real one and the load is a valid address whose value is ignored.
+                constexpr int AHEAD = 3;
+                const float* xV = sV + (roleB ? lo : (lo + 2)) * LD + vrow;
+                const float2* xP = sP + (roleB ? lo : (lo + 2));
+                float oE, oD, oV = 0.f;
+#define BED_STEPH(q_, y_, k_)                                                       \
+                do {                                                            \
+                    const float e_in = upper_from_lane31(q_.x, prevE);          \
+                    const float d_in = upper_from_lane31(q_.y, prevD);          \
+                    const float y_in = WANT_V ? upper_from_lower(y_, prevV) : 0.f; \
+                    chain_rotate<WANT_V>(S, e_in, d_in, y_in, oE, oD, oV);      \
+                    q_ = xP[(k_) + AHEAD];                                      \
+                    if (WANT_V) y_ = xV[((k_) + AHEAD) * LD];                   \
+                    const_cast<float2*>(xP)[(k_)] = make_float2(oE, oD);        \
+                    if (WANT_V) const_cast<float*>(xV)[(k_) * LD] = oV;         \
+                    prevE = oE;                                                 \
+                    prevD = oD;                                                 \
+                    prevV = oV;                                                 \
+                } while (0)
+                int t = lo + 2;
+                for (; t + 1 < hi; t += 2) {
+                    BED_STEPH(q0, y0, 0);
+                    BED_STEPH(q1, y1, 1);
+                    xV += 2 * LD;
+                    xP += 2;
+                }
+                if (t < hi) {
+                    BED_STEPH(q0, y0, 0);
+                    xV += LD;
+                    xP += 1;
+                }
+#undef BED_STEPH
+                BED_PROBE(4);
+                // The three closing steps belong to B alone; the A lanes' stores would now land
+                // beyond the window, so they are parked in the padding behind the arrays.
+                xV = roleB ? xV : (sV + (N + 3) * LD + vrow);
+                xP = roleB ? xP : (sP + (N + 3));
+                // t = hi: A closes (values taken before its state is overwritten); B rotates row hi-2
+                float fE, fD, fV;
+                chain_finish(S, fE, fD, fV);
+                chain_rotate<WANT_V>(S, upper_from_lane31(prevE, prevE), upper_from_lane31(prevD, prevD),
+                                     WANT_V ? upper_from_lower(prevV, prevV) : 0.f, oE, oD, oV);
+                const_cast<float2*>(xP)[0] = make_float2(oE, oD);
+                if (WANT_V) const_cast<float*>(xV)[0] = oV;
+                // t = hi + 1: B rotates row hi-1 with A's closing values
+                chain_rotate<WANT_V>(S, upper_from_lane31(fE, fE), upper_from_lane31(fD, fD),
+                                     WANT_V ? upper_from_lower(fV, fV) : 0.f, oE, oD, oV);
+                const_cast<float2*>(xP)[1] = make_float2(oE, oD);
+                if (WANT_V) const_cast<float*>(xV)[LD] = oV;
+                // t = hi + 2: B closes
+                chain_finish(S, fE, fD, fV);
+                const_cast<float2*>(xP)[2] = make_float2(fE, fD);
+                if (WANT_V) const_cast<float*>(xV)[2 * LD] = fV;
+                rotations += 2u * (uint32_t)(hi - lo);
+                sweeps += 2;
+                BED_PROBE(5);
+            } else {
+                // Rows need the whole wavefront.  The scalar recurrences of the two sweeps
+                // still run in the two halves (lanes 0..31 sweep A, lanes 32..63 sweep B, two
+                // rotations behind), but every lane owns a row of V: the rotation coefficients
+                // of both sweeps are broadcast with v_readlane and every lane applies both
+                // rotations to its row.
+                const float sD = pD;                       // d'[lo] as left by A
+                float xB = pV;                             // column lo as left by A: B's carried column
+                // t = lo + 1: A rotates row lo+1 (still computed by every lane)
+                chain_rotate<WANT_V>(A, q1.x, q1.y, y1, pE, pD, pV);
+                BED_REFILL(q1, y1, lo + 1);
+                BED_PROBE(3);
+                Chain S;                                   // this lane's recurrence: A or B (no V part)
+                S.g = roleB ? (sD - mu2) : A.g;
+                S.s = roleB ? 1.f : A.s;
+                S.c = roleB ? 1.f : A.c;
+                S.p = roleB ? 0.f : A.p;
+                S.dk = roleB ? sD : A.dk;
+                S.x = 0.f;
+                float xA = A.x;                            // A's carried column
+                float prevE = pE, prevD = pD;              // A's (e, d) of the previous step; pV is its column
+                // T: one running pointer per lane as in the half-wavefront loop (store at the
+                // pointer, load three positions above).  V: every lane stores column t-2 and
+                // prefetches column t+3 of its own row.
+                constexpr int AHEAD = 3;
+                const float2* xP = sP + (roleB ? lo : (lo + 2));
+                float* xVp = sV + lo * LD + vrow;
+                float oE, oD, unused;
+#define BED_STEPW(q_, y_, k_)                                                       \
+                do {                                                            \
+                    const float e_in = upper_from_lane31(q_.x, prevE);          \
+                    const float d_in = upper_from_lane31(q_.y, prevD);          \
+                    chain_rotate<false>(S, e_in, d_in, 0.f, oE, oD, unused);    \
+                    if (WANT_V) {                                               \
+                        const float cA = read_lane(S.c, 0), sA = read_lane(S.s, 0);   \
+                        const float cB = read_lane(S.c, 32), sB = read_lane(S.s, 32); \
+                        const float nV = fmaf(cA, xA, sA * y_);                 \
+                        xA = fmaf(cA, y_, -sA * xA);                            \
+                        const float vo = fmaf(cB, xB, sB * pV);                 \
+                        xB = fmaf(cB, pV, -sB * xB);                            \
+                        pV = nV;                                                \
+                        xVp[(k_) * LD] = vo;                                    \
+                        y_ = xVp[((k_) + 5) * LD];                              \
+                    }                                                           \
+                    q_ = xP[(k_) + AHEAD];                                      \
+                    const_cast<float2*>(xP)[(k_)] = make_float2(oE, oD);        \
+                    prevE = oE;                                                 \
+                    prevD = oD;                                                 \
+                } while (0)
+                int t = lo + 2;
+                for (; t + 1 < hi; t += 2) {
+                    BED_STEPW(q0, y0, 0);
+                    BED_STEPW(q1, y1, 1);
+                    xVp += 2 * LD;
+                    xP += 2;
+                }
+                if (t < hi) {
+                    BED_STEPW(q0, y0, 0);
+                    xVp += LD;
+                    xP += 1;
+                }
+#undef BED_STEPW
+                BED_PROBE(4);
+                // closing steps: B alone; the A lanes' T stores are parked in the padding
+                xP = roleB ? xP : (sP + (N + 3));
+                float fE, fD, fx;
+                chain_finish(S, fE, fD, fx);               // A lanes: e[hi-1], d[hi] as left by A
+                // t = hi: B rotates row hi-2 with A's outputs of row hi-1
+                chain_rotate<false>(S, upper_from_lane31(prevE, prevE), upper_from_lane31(prevD, prevD), 0.f,
+                                    oE, oD, unused);
+                const_cast<float2*>(xP)[0] = make_float2(oE, oD);
+                if (WANT_V) {
+                    const float cB = read_lane(S.c, 32), sB = read_lane(S.s, 32);
+                    xVp[0] = fmaf(cB, xB, sB * pV);
+                    xB = fmaf(cB, pV, -sB * xB);
+                }
+                // t = hi + 1: B rotates row hi-1 with A's closing values (column hi as left by A is xA)
+                chain_rotate<false>(S, upper_from_lane31(fE, fE), upper_from_lane31(fD, fD), 0.f, oE, oD, unused);
+                const_cast<float2*>(xP)[1] = make_float2(oE, oD);
+                if (WANT_V) {
+                    const float cB = read_lane(S.c, 32), sB = read_lane(S.s, 32);
+                    xVp[LD] = fmaf(cB, xB, sB * xA);
+                    xB = fmaf(cB, xA, -sB * xB);
+                }
+                // t = hi + 2: B closes
+                chain_finish(S, fE, fD, fx);
+                const_cast<float2*>(xP)[2] = make_float2(fE, fD);
+                if (WANT_V) xVp[2 * LD] = xB;
+                rotations += 2u * (uint32_t)(hi - lo);
+                sweeps += 2;
+                BED_PROBE(5);
+            }
+        }
+#undef BED_REFILL
+        wave_sync();
+    }
+    BED_PROBE_DUMP();
+    info = 0;
+#pragma unroll
+    for (int bk = 0; bk < NB; ++bk) {
+        // a non-finite eigenvalue (NaN/Inf input) is reported even when every off-diagonal deflated
+        const uint64_t bad = __ballot(lane + 64 * bk < n && !(fabsf(dl[bk]) < __builtin_inff()));
+        info += max((int)__builtin_popcountll(nz[bk]), (int)__builtin_popcountll(bad));
+        d_lane[bk] = dl[bk];
+    }
+    (void)args;
+    (void)b;
+}
+
+// ---------------------------------------------------------------------------
 // N      register-array size (4, 8, 16, 24, 32, 48, 64); n <= N at run time
 // WANT_V accumulate eigenvectors
 // STAGE  kFull, kTridiagOnly (stage hook 1), kQrOnly (stage hook 2)
@@ -461,274 +775,10 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         }
     } else {
         // ---- shifted QR iterations on the tridiagonal in sP ----
+        float d_lane[1];
+        qr_iterations<N, HALF, WANT_V, LD>(sP, sV, lane, row, n, rotations, info, d_lane, args, b);
+        const float dl = d_lane[0];
         const int vrow = row;
-        const bool roleB = lane >= 32;
-        const uint32_t cap = 30u * (uint32_t)n;
-        uint32_t sweeps = 0;
-        bool live = lane < n - 1;      // e[lane] not yet deflated
-        uint64_t nz = 0;
-        float dl = 0.f;
-        BED_PROBE_INIT();
-        while (true) {
-            BED_PROBE(0);
-            // deflation test, one off-diagonal per lane: lane k looks at e[k], d[k], d[k+1]
-            float el = 0.f, dnext = 0.f;
-            if (lane < N) {
-                const float2 pk = sP[lane];
-                const float2 pk1 = sP[lane + 1];
-                dl = pk.y;
-                el = pk1.x;
-                dnext = pk1.y;
-            }
-            live = live && !(fabsf(el) <= fmaxf(kEps * (fabsf(dl) + fabsf(dnext)), kTinyE));
-            nz = __ballot(live);
-            if (nz == 0 || sweeps >= cap) break;
-            const int hi = 64 - __builtin_clzll(nz);          // e[hi-1] is the last live entry
-            const uint64_t below = ~nz & ((1ull << (hi - 1)) - 1ull);
-            const int lo = below ? 64 - __builtin_clzll(below) : 0;
-
-            BED_PROBE(1);
-            // eigenvalues of the trailing block [[ta, tb], [tb, td]] (App. A.3), smaller-angle root first
-            const float ta = read_lane(dl, hi - 1);
-            const float tb = read_lane(el, hi - 1);
-            const float td = read_lane(dnext, hi - 1);
-            const float delta = 0.5f * (ta - td);
-            const float rt = __builtin_amdgcn_sqrtf(fmaf(delta, delta, tb * tb));
-            const float den = delta + ((delta >= 0.f) ? rt : -rt);
-            const float tt = (tb * tb) * __builtin_amdgcn_rcpf(den);
-            const float mu1 = td - tt;          // eigenvalue closer to the last diagonal entry
-            const float mu2 = ta + tt;          // the other eigenvalue of the block
-
-            // Inputs of rotation t: (e[t], d[t+1]) = sP[t+1] and column t+1 of V.  They are
-            // fetched two rotations ahead into two slots used in alternation (slot 0: rotations
-            // lo, lo+2, ...; slot 1: rotations lo+1, lo+3, ...), so a slot is refilled right after
-            // it has been consumed and no register shuffling is needed.
-            const float d_lo = read_lane(dl, lo);
-            float2 q0 = make_float2(read_lane(el, lo), read_lane(dnext, lo));
-            float2 q1 = sP[lo + 2];
-            float y0 = 0.f, y1 = 0.f;
-            Chain A;
-            chain_start<WANT_V>(A, d_lo, mu1, WANT_V ? sV[lo * LD + vrow] : 0.f);
-            if (WANT_V) {
-                y0 = sV[(lo + 1) * LD + vrow];
-                y1 = sV[(lo + 2) * LD + vrow];
-            }
-            // refill a slot with the inputs of rotation t_+2 (indices stay inside the padding)
-#define BED_REFILL(q_, y_, t_)                                  \
-            do {                                                \
-                q_ = sP[(t_) + 3];                              \
-                if (WANT_V) y_ = sV[((t_) + 3) * LD + vrow];    \
-            } while (0)
-
-            {
-                // Two sweeps (shift mu1, then mu2) over the same window, software-pipelined:
-                // sweep B runs two rotations behind sweep A and takes A's results straight
-                // from registers.  At step t: B handles row t-2 with A's outputs of step t-1,
-                // while A handles row t.
-                float pE, pD, pV = 0.f;     // A's outputs of the previous step
-                BED_PROBE(2);
-                // t = lo: A rotates row lo
-                chain_rotate<WANT_V>(A, q0.x, q0.y, y0, pE, pD, pV);
-                BED_REFILL(q0, y0, lo);
-                if (hi - lo == 1) {
-                    // The window is the 2x2 block the shifts were taken from: the step with
-                    // its exact eigenvalue mu1 diagonalises it (this is the rotation of
-                    // App. A.3), so the off-diagonal is set to zero and no second sweep runs.
-                    // (A second sweep here would start from (d'[lo] - mu2, e'[lo]) = rounding
-                    // noise and could rotate the converged block by an arbitrary angle.)
-                    sP[lo] = make_float2(pE, pD);
-                    if (WANT_V) sV[lo * LD + vrow] = pV;
-                    chain_finish(A, pE, pD, pV);
-                    sP[hi] = make_float2(0.f, pD);
-                    if (WANT_V) sV[hi * LD + vrow] = pV;
-                    rotations += 1u;
-                    sweeps += 1;
-                    BED_PROBE(5);
-                } else if (HALF) {
-                    // Role lanes: lanes 0..31 carry sweep A, lanes 32..63 carry sweep B, so one
-                    // instruction stream advances both sweeps by one rotation per step.
-                    // B's inputs are A's outputs of the previous step, copied from the lower
-                    // half of the wavefront.
-                    const float sD = pD, sX = pV;              // d'[lo], column lo as left by A
-                    // t = lo + 1: A rotates row lo+1 (still computed by every lane)
-                    chain_rotate<WANT_V>(A, q1.x, q1.y, y1, pE, pD, pV);
-                    BED_REFILL(q1, y1, lo + 1);
-                    BED_PROBE(3);
-                    Chain S;                                   // this lane's chain: A or B
-                    S.g = roleB ? (sD - mu2) : A.g;
-                    S.s = roleB ? 1.f : A.s;
-                    S.c = roleB ? 1.f : A.c;
-                    S.p = roleB ? 0.f : A.p;
-                    S.dk = roleB ? sD : A.dk;
-                    S.x = roleB ? sX : A.x;
-                    // B's inputs are A's outputs of the previous step.  e and d are uniform over the
-                    // A lanes: one DPP broadcast of lane 31 into the upper half merges them with the A
-                    // lanes' own inputs.  The V entry is per row: a half swap does the same merge.
-                    float prevE = pE, prevD = pD, prevV = pV;
-                    // One running LDS pointer per lane and array; every lane stores at the pointer
-                    // and loads three positions above it.  A lanes: the pointer is at position t,
-                    // so the load fetches the inputs of rotation t+2 (position t+3) and the store
-                    // lands on a position A has already consumed and B overwrites with the final
-                    // value two steps later.  B lanes: the pointer is at position t-2, so the
-                    // store is the real one and the load is a valid address whose value is ignored.
-                    constexpr int AHEAD = 3;
-                    const float* xV = sV + (roleB ? lo : (lo + 2)) * LD + vrow;
-                    const float2* xP = sP + (roleB ? lo : (lo + 2));
-                    float oE, oD, oV = 0.f;
-#define BED_STEPH(q_, y_, k_)                                                       \
-                    do {                                                            \
-                        const float e_in = upper_from_lane31(q_.x, prevE);          \
-                        const float d_in = upper_from_lane31(q_.y, prevD);          \
-                        const float y_in = WANT_V ? upper_from_lower(y_, prevV) : 0.f; \
-                        chain_rotate<WANT_V>(S, e_in, d_in, y_in, oE, oD, oV);      \
-                        q_ = xP[(k_) + AHEAD];                                      \
-                        if (WANT_V) y_ = xV[((k_) + AHEAD) * LD];                   \
-                        const_cast<float2*>(xP)[(k_)] = make_float2(oE, oD);        \
-                        if (WANT_V) const_cast<float*>(xV)[(k_) * LD] = oV;         \
-                        prevE = oE;                                                 \
-                        prevD = oD;                                                 \
-                        prevV = oV;                                                 \
-                    } while (0)
-                    int t = lo + 2;
-                    for (; t + 1 < hi; t += 2) {
-                        BED_STEPH(q0, y0, 0);
-                        BED_STEPH(q1, y1, 1);
-                        xV += 2 * LD;
-                        xP += 2;
-                    }
-                    if (t < hi) {
-                        BED_STEPH(q0, y0, 0);
-                        xV += LD;
-                        xP += 1;
-                    }
-#undef BED_STEPH
-                    BED_PROBE(4);
-                    // The three closing steps belong to B alone; the A lanes' stores would now land
-                    // beyond the window, so they are parked in the padding behind the arrays.
-                    xV = roleB ? xV : (sV + (N + 3) * LD + vrow);
-                    xP = roleB ? xP : (sP + (N + 3));
-                    // t = hi: A closes (values taken before its state is overwritten); B rotates row hi-2
-                    float fE, fD, fV;
-                    chain_finish(S, fE, fD, fV);
-                    chain_rotate<WANT_V>(S, upper_from_lane31(prevE, prevE), upper_from_lane31(prevD, prevD),
-                                         WANT_V ? upper_from_lower(prevV, prevV) : 0.f, oE, oD, oV);
-                    const_cast<float2*>(xP)[0] = make_float2(oE, oD);
-                    if (WANT_V) const_cast<float*>(xV)[0] = oV;
-                    // t = hi + 1: B rotates row hi-1 with A's closing values
-                    chain_rotate<WANT_V>(S, upper_from_lane31(fE, fE), upper_from_lane31(fD, fD),
-                                         WANT_V ? upper_from_lower(fV, fV) : 0.f, oE, oD, oV);
-                    const_cast<float2*>(xP)[1] = make_float2(oE, oD);
-                    if (WANT_V) const_cast<float*>(xV)[LD] = oV;
-                    // t = hi + 2: B closes
-                    chain_finish(S, fE, fD, fV);
-                    const_cast<float2*>(xP)[2] = make_float2(fE, fD);
-                    if (WANT_V) const_cast<float*>(xV)[2 * LD] = fV;
-                    rotations += 2u * (uint32_t)(hi - lo);
-                    sweeps += 2;
-                    BED_PROBE(5);
-                } else {
-                    // Rows need the whole wavefront.  The scalar recurrences of the two sweeps
-                    // still run in the two halves (lanes 0..31 sweep A, lanes 32..63 sweep B, two
-                    // rotations behind), but every lane owns a row of V: the rotation coefficients
-                    // of both sweeps are broadcast with v_readlane and every lane applies both
-                    // rotations to its row.
-                    const float sD = pD;                       // d'[lo] as left by A
-                    float xB = pV;                             // column lo as left by A: B's carried column
-                    // t = lo + 1: A rotates row lo+1 (still computed by every lane)
-                    chain_rotate<WANT_V>(A, q1.x, q1.y, y1, pE, pD, pV);
-                    BED_REFILL(q1, y1, lo + 1);
-                    BED_PROBE(3);
-                    Chain S;                                   // this lane's recurrence: A or B (no V part)
-                    S.g = roleB ? (sD - mu2) : A.g;
-                    S.s = roleB ? 1.f : A.s;
-                    S.c = roleB ? 1.f : A.c;
-                    S.p = roleB ? 0.f : A.p;
-                    S.dk = roleB ? sD : A.dk;
-                    S.x = 0.f;
-                    float xA = A.x;                            // A's carried column
-                    float prevE = pE, prevD = pD;              // A's (e, d) of the previous step; pV is its column
-                    // T: one running pointer per lane as in the half-wavefront loop (store at the
-                    // pointer, load three positions above).  V: every lane stores column t-2 and
-                    // prefetches column t+3 of its own row.
-                    constexpr int AHEAD = 3;
-                    const float2* xP = sP + (roleB ? lo : (lo + 2));
-                    float* xVp = sV + lo * LD + vrow;
-                    float oE, oD, unused;
-#define BED_STEPW(q_, y_, k_)                                                       \
-                    do {                                                            \
-                        const float e_in = upper_from_lane31(q_.x, prevE);          \
-                        const float d_in = upper_from_lane31(q_.y, prevD);          \
-                        chain_rotate<false>(S, e_in, d_in, 0.f, oE, oD, unused);    \
-                        if (WANT_V) {                                               \
-                            const float cA = read_lane(S.c, 0), sA = read_lane(S.s, 0);   \
-                            const float cB = read_lane(S.c, 32), sB = read_lane(S.s, 32); \
-                            const float nV = fmaf(cA, xA, sA * y_);                 \
-                            xA = fmaf(cA, y_, -sA * xA);                            \
-                            const float vo = fmaf(cB, xB, sB * pV);                 \
-                            xB = fmaf(cB, pV, -sB * xB);                            \
-                            pV = nV;                                                \
-                            xVp[(k_) * LD] = vo;                                    \
-                            y_ = xVp[((k_) + 5) * LD];                              \
-                        }                                                           \
-                        q_ = xP[(k_) + AHEAD];                                      \
-                        const_cast<float2*>(xP)[(k_)] = make_float2(oE, oD);        \
-                        prevE = oE;                                                 \
-                        prevD = oD;                                                 \
-                    } while (0)
-                    int t = lo + 2;
-                    for (; t + 1 < hi; t += 2) {
-                        BED_STEPW(q0, y0, 0);
-                        BED_STEPW(q1, y1, 1);
-                        xVp += 2 * LD;
-                        xP += 2;
-                    }
-                    if (t < hi) {
-                        BED_STEPW(q0, y0, 0);
-                        xVp += LD;
-                        xP += 1;
-                    }
-#undef BED_STEPW
-                    BED_PROBE(4);
-                    // closing steps: B alone; the A lanes' T stores are parked in the padding
-                    xP = roleB ? xP : (sP + (N + 3));
-                    float fE, fD, fx;
-                    chain_finish(S, fE, fD, fx);               // A lanes: e[hi-1], d[hi] as left by A
-                    // t = hi: B rotates row hi-2 with A's outputs of row hi-1
-                    chain_rotate<false>(S, upper_from_lane31(prevE, prevE), upper_from_lane31(prevD, prevD), 0.f,
-                                        oE, oD, unused);
-                    const_cast<float2*>(xP)[0] = make_float2(oE, oD);
-                    if (WANT_V) {
-                        const float cB = read_lane(S.c, 32), sB = read_lane(S.s, 32);
-                        xVp[0] = fmaf(cB, xB, sB * pV);
-                        xB = fmaf(cB, pV, -sB * xB);
-                    }
-                    // t = hi + 1: B rotates row hi-1 with A's closing values (column hi as left by A is xA)
-                    chain_rotate<false>(S, upper_from_lane31(fE, fE), upper_from_lane31(fD, fD), 0.f, oE, oD, unused);
-                    const_cast<float2*>(xP)[1] = make_float2(oE, oD);
-                    if (WANT_V) {
-                        const float cB = read_lane(S.c, 32), sB = read_lane(S.s, 32);
-                        xVp[LD] = fmaf(cB, xB, sB * xA);
-                        xB = fmaf(cB, xA, -sB * xB);
-                    }
-                    // t = hi + 2: B closes
-                    chain_finish(S, fE, fD, fx);
-                    const_cast<float2*>(xP)[2] = make_float2(fE, fD);
-                    if (WANT_V) xVp[2 * LD] = xB;
-                    rotations += 2u * (uint32_t)(hi - lo);
-                    sweeps += 2;
-                    BED_PROBE(5);
-                }
-            }
-#undef BED_REFILL
-            wave_sync();
-        }
-        BED_PROBE_DUMP();
-        info = __builtin_popcountll(nz);
-        {
-            // a non-finite eigenvalue (NaN/Inf input) is reported even when every off-diagonal deflated
-            const uint64_t bad = __ballot(lane < n && !(fabsf(dl) < __builtin_inff()));
-            info = max(info, (int)__builtin_popcountll(bad));
-        }
 
         if (STAGE == kSpectral) {
             // ---- F = V f(Lambda) V^T (Sec. 4.2-4.4, App. B: A^{-1/2} for whitening, A^{1/2} for
