@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libbed.so")
 _lib = None
 
-BED_MAX_N = 64
+BED_MAX_N = 128
 
 
 class BedError(RuntimeError):

@@ -11,6 +11,7 @@ hipError_t launch_wave_n24(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n32(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n48(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n64(const KernelArgs&, int, bool, hipStream_t);
+hipError_t launch_block(const KernelArgs&, int, bool, hipStream_t);
 
 hipError_t launch(const KernelArgs& args, int stage, bool want_v, hipStream_t stream) {
     if (args.batch == 0) return hipSuccess;
@@ -26,7 +27,8 @@ hipError_t launch(const KernelArgs& args, int stage, bool want_v, hipStream_t st
     if (n <= 24) return launch_wave_n24(args, stage, want_v, stream);
     if (n <= 32) return launch_wave_n32(args, stage, want_v, stream);
     if (n <= 48) return launch_wave_n48(args, stage, want_v, stream);
-    return launch_wave_n64(args, stage, want_v, stream);
+    if (n <= 64) return launch_wave_n64(args, stage, want_v, stream);
+    return launch_block(args, stage, want_v, stream);     // 64 < n <= 128: four wavefronts per matrix
 }
 
 }  // namespace bed

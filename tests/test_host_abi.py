@@ -49,7 +49,7 @@ def test_argument_validation_is_host_side(lib):
     assert lib.bed_syevd(A, 1, 4, None, V, None) == -1          # NULL evals
     assert lib.bed_syevd(A, -1, 4, L, V, None) == -2            # batch < 0
     assert lib.bed_syevd(A, 1, 0, L, V, None) == -3             # n < 1
-    assert lib.bed_syevd(A, 1, 65, L, V, None) == -3            # n > 64
+    assert lib.bed_syevd(A, 1, 129, L, V, None) == -3           # n > 128
     assert lib.bed_syevd(p(0x10002), 1, 4, L, V, None) == -4    # misaligned
     assert lib.bed_syevd(A, 1, 4, L, p(0x10010), None) == -6    # evecs overlaps A
     assert lib.bed_syevd(A, 0, 4, L, V, None) == 0              # batch 0: no-op
@@ -66,7 +66,7 @@ def test_argument_validation_is_host_side(lib):
     assert lib.bed_spd_fn(A, 1, 4, 0, f(-1.0), V, None, None, None) == -7          # negative floor
     assert lib.bed_spd_fn(A, 1, 4, 0, f(float("nan")), V, None, None, None) == -7  # NaN floor
     assert lib.bed_spd_fn(A, 1, 4, 0, f(float("inf")), V, None, None, None) == -7  # infinite floor
-    assert lib.bed_spd_fn(A, 1, 65, 0, f(0.0), V, None, None, None) == -3
+    assert lib.bed_spd_fn(A, 1, 129, 0, f(0.0), V, None, None, None) == -3
     assert lib.bed_spd_fn(A, 1, 4, 0, f(0.0), p(0x10020), None, None, None) == -6  # out overlaps A
     assert lib.bed_spd_fn(A, 0, 4, 0, f(0.0), V, None, None, None) == 0
     O = p(0x50000)
@@ -76,7 +76,8 @@ def test_argument_validation_is_host_side(lib):
     assert lib.bed_syevd_backward(L, V, L, None, 1, 4, 1, 65, f(0.0), O, None) == -7        # degree out of range
     assert lib.bed_syevd_backward(L, V, L, None, 1, 4, 0, 9, f(float("nan")), O, None) == -7
     assert lib.bed_syevd_backward(L, V, L, None, 1, 4, 0, 9, f(0.0), V, None) == -6         # output aliases evecs
-    assert lib.bed_syevd_backward(L, V, L, None, 1, 65, 0, 9, f(0.0), O, None) == -3
+    assert lib.bed_syevd_backward(L, V, L, None, 1, 65, 0, 9, f(0.0), O, None) == -3         # gradients: n <= 64
+    assert lib.bed_spd_fn_backward(L, V, A, 1, 65, 0, f(0.0), O, None) == -3
     assert lib.bed_syevd_backward(L, V, L, None, 0, 4, 0, 9, f(0.0), O, None) == 0
     assert lib.bed_spd_fn_backward(L, V, None, 1, 4, 0, f(0.0), O, None) == -1
     assert lib.bed_spd_fn_backward(L, V, A, 1, 4, 1, f(0.0), O, None) == -7                 # inverse sqrt, floor 0
