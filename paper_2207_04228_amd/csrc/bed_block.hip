@@ -28,7 +28,8 @@ __global__ __launch_bounds__(BT) void block_kernel(KernelArgs args) {
     __shared__ float sV[(BN + 8) * BLD];         // P, then V: V[r][c] at sV[c * BLD + r]
     __shared__ float2 sP_all[4 * BPA];           // one copy of T per wavefront: sP[k] = (e[k-1], d[k])
     __shared__ float sd[BN], se[BN];             // T as produced by the tridiagonalisation
-    __shared__ float svec[BN], sq[BN];           // u and q of the current step
+    __shared__ __align__(16) float svec[BN];     // u of the current step
+    __shared__ __align__(16) float sq[BN];       // q of the current step
     __shared__ float sred[8];
     __shared__ int sinv[BN];
 
@@ -54,7 +55,13 @@ __global__ __launch_bounds__(BT) void block_kernel(KernelArgs args) {
         __syncthreads();
         float scale;
         pow2_scale(fmaxf(fmaxf(sred[0], sred[1]), fmaxf(sred[2], sred[3])), scale, inv_scale);
-        // ---- load: lower triangle mirrored, scaled; P = I ----
+        // ---- load: lower triangle mirrored, scaled; P = I.  Rows and columns n .. 127 are
+        // zero, so the loops below can run over whole groups of eight columns. ----
+        for (int idx = tid; idx < BN * BLD; idx += BT) {
+            sA[idx] = 0.f;
+            if (WANT_V) sV[idx] = 0.f;
+        }
+        __syncthreads();
         for (int idx = tid; idx < n * n; idx += BT) {
             const int i = (int)(((float)idx + 0.5f) * rcp_n);
             const int j = idx - i * n;
@@ -63,20 +70,27 @@ __global__ __launch_bounds__(BT) void block_kernel(KernelArgs args) {
                 sA[j * BLD + i] = a;
                 sA[i * BLD + j] = a;
             }
-            if (WANT_V) sV[j * BLD + i] = (i == j) ? 1.f : 0.f;
+            if (WANT_V && i == j) sV[j * BLD + i] = 1.f;
         }
         __syncthreads();
 
         // ---- Householder tridiagonalisation, column J reduced at step J (Sec. 3.1) ----
+        // The column loops run in groups of eight from the group that holds column J+1 to the
+        // group that holds column n-1: eight independent LDS loads are in flight per group and
+        // u, q come as 128-bit broadcast reads.  Columns <= J inside the first group are dead
+        // for A (their entries of T are already recorded) and have u = 0, so P is untouched.
+        // (Holding the rows in 128 VGPRs with unrolled column loops was measured too: the
+        // step body then no longer fits the instruction cache and the phase gets slower.)
         const bool isA = tid < BN;
         const int row = tid & (BN - 1);
-        const bool rowok = row < n;
-        float* const X = isA ? sA : sV;            // this thread's row: X[c * BLD + row]
-        const bool works = rowok && (isA || WANT_V);
+        float* const X = (isA ? sA : sV) + row;    // this thread's row: X[c * BLD]
+        const bool works = isA || WANT_V;
+        const int cend = (n + 7) & ~7;
         for (int J = 0; J < n - 2; ++J) {
+            const int c0 = (J + 1) & ~7;
             float xc = 0.f;
             if (isA) {
-                xc = (rowok && row > J) ? sA[J * BLD + row] : 0.f;
+                xc = (row > J) ? sA[J * BLD + row] : 0.f;
                 const float part = wave_sum<64>(xc * xc);
                 if (lane == 0) sred[wv] = part;
             }
@@ -101,21 +115,46 @@ __global__ __launch_bounds__(BT) void block_kernel(KernelArgs args) {
             // p = 2 A u / |u|^2 (A rows), w = 2 P u / |u|^2 (P rows)
             float pw = 0.f;
             if (works) {
-                float acc0 = 0.f, acc1 = 0.f;
-                int c = J + 1;
-                for (; c + 1 < n; c += 2) {
-                    acc0 = fmaf(X[c * BLD + row], svec[c], acc0);
-                    acc1 = fmaf(X[(c + 1) * BLD + row], svec[c + 1], acc1);
+                float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 2
+                for (int c = c0; c < cend; c += 8) {
+                    float xv[8];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) xv[k] = X[(c + k) * BLD];
+                    const float4 u0 = *reinterpret_cast<const float4*>(svec + c);
+                    const float4 u1 = *reinterpret_cast<const float4*>(svec + c + 4);
+                    acc[0] = fmaf(xv[0], u0.x, acc[0]);
+                    acc[1] = fmaf(xv[1], u0.y, acc[1]);
+                    acc[2] = fmaf(xv[2], u0.z, acc[2]);
+                    acc[3] = fmaf(xv[3], u0.w, acc[3]);
+                    acc[0] = fmaf(xv[4], u1.x, acc[0]);
+                    acc[1] = fmaf(xv[5], u1.y, acc[1]);
+                    acc[2] = fmaf(xv[6], u1.z, acc[2]);
+                    acc[3] = fmaf(xv[7], u1.w, acc[3]);
                 }
-                if (c < n) acc0 = fmaf(X[c * BLD + row], svec[c], acc0);
-                pw = beta * (acc0 + acc1);
+                pw = beta * ((acc[0] + acc[1]) + (acc[2] + acc[3]));
             }
             if (isA) {
                 const float part = wave_sum<64>(ur * pw);
                 if (lane == 0) sred[4 + wv] = part;
-            } else if (works) {
+            } else if (WANT_V) {
                 // P <- P - w u^T
-                for (int c = J + 1; c < n; ++c) X[c * BLD + row] = fmaf(-pw, svec[c], X[c * BLD + row]);
+#pragma unroll 2
+                for (int c = c0; c < cend; c += 8) {
+                    float xv[8];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) xv[k] = X[(c + k) * BLD];
+                    const float4 u0 = *reinterpret_cast<const float4*>(svec + c);
+                    const float4 u1 = *reinterpret_cast<const float4*>(svec + c + 4);
+                    X[(c + 0) * BLD] = fmaf(-pw, u0.x, xv[0]);
+                    X[(c + 1) * BLD] = fmaf(-pw, u0.y, xv[1]);
+                    X[(c + 2) * BLD] = fmaf(-pw, u0.z, xv[2]);
+                    X[(c + 3) * BLD] = fmaf(-pw, u0.w, xv[3]);
+                    X[(c + 4) * BLD] = fmaf(-pw, u1.x, xv[4]);
+                    X[(c + 5) * BLD] = fmaf(-pw, u1.y, xv[5]);
+                    X[(c + 6) * BLD] = fmaf(-pw, u1.z, xv[6]);
+                    X[(c + 7) * BLD] = fmaf(-pw, u1.w, xv[7]);
+                }
             }
             __syncthreads();
             float q = 0.f;
@@ -125,10 +164,26 @@ __global__ __launch_bounds__(BT) void block_kernel(KernelArgs args) {
                 sq[row] = q;
             }
             __syncthreads();
-            if (isA && rowok) {
+            if (isA) {
                 // A <- A - q u^T - u q^T
-                for (int c = J + 1; c < n; ++c)
-                    sA[c * BLD + row] = fmaf(-ur, sq[c], fmaf(-q, svec[c], sA[c * BLD + row]));
+#pragma unroll 2
+                for (int c = c0; c < cend; c += 8) {
+                    float xv[8];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) xv[k] = X[(c + k) * BLD];
+                    const float4 u0 = *reinterpret_cast<const float4*>(svec + c);
+                    const float4 u1 = *reinterpret_cast<const float4*>(svec + c + 4);
+                    const float4 q0 = *reinterpret_cast<const float4*>(sq + c);
+                    const float4 q1 = *reinterpret_cast<const float4*>(sq + c + 4);
+                    X[(c + 0) * BLD] = fmaf(-ur, q0.x, fmaf(-q, u0.x, xv[0]));
+                    X[(c + 1) * BLD] = fmaf(-ur, q0.y, fmaf(-q, u0.y, xv[1]));
+                    X[(c + 2) * BLD] = fmaf(-ur, q0.z, fmaf(-q, u0.z, xv[2]));
+                    X[(c + 3) * BLD] = fmaf(-ur, q0.w, fmaf(-q, u0.w, xv[3]));
+                    X[(c + 4) * BLD] = fmaf(-ur, q1.x, fmaf(-q, u1.x, xv[4]));
+                    X[(c + 5) * BLD] = fmaf(-ur, q1.y, fmaf(-q, u1.y, xv[5]));
+                    X[(c + 6) * BLD] = fmaf(-ur, q1.z, fmaf(-q, u1.z, xv[6]));
+                    X[(c + 7) * BLD] = fmaf(-ur, q1.w, fmaf(-q, u1.w, xv[7]));
+                }
             }
             // the next step's first barrier orders these updates before other threads read them
         }
