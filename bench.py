@@ -197,15 +197,18 @@ def main(argv=None) -> int:
             reps) * 1e6
         extras["spd_inv_sqrt_backward_us"][str(n)] = timed(
             lambda: binding.bed_spd_fn_backward(ev, V, gV, binding.BED_FN_INV_SQRT, 1e-6, grad_A=F), reps) * 1e6
-    for n, batch in (() if a.no_extras else ((4, 65536), (8, 65536), (16, 4096), (32, 4096))):
-        Ab = torch.from_numpy(workloads.config2(batch) if n == 4 else workloads.config3(n, batch=batch)).to(dev)
+    for n, batch in (() if a.no_extras else ((4, 65536), (8, 65536), (16, 4096), (32, 4096), (64, 256), (128, 256))):
+        A32b = (workloads.config2(batch) if n == 4 else
+                workloads.config3(n, batch=batch) if n <= 32 else
+                workloads.config5(n, batch=batch) if n == 64 else workloads.covariance(batch, n, 4 * n, 1e-4, 1))
+        Ab = torch.from_numpy(A32b).to(dev)
         evb = torch.empty((batch, n), dtype=torch.float32, device=dev)
         Vb = torch.empty((batch, n, n), dtype=torch.float32, device=dev)
         t = timed(lambda: binding.bed_syevd(Ab, evb, Vb), 10)
         extras["large_batch"][f"n{n}_b{batch}"] = {
             "kernel_us": t * 1e6, "matrices_per_s": batch / t,
             "gbs": batch * bytes_per_matrix(n) / t / 1e9}
-        del Ab, evb, Vb
+        del Ab, evb, Vb, A32b
 
     dom = per_n["32"]
     # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary
