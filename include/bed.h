@@ -24,7 +24,6 @@ extern "C" {
 #endif
 
 #define BED_MAX_N 128
-#define BED_MAX_N_GRAD 64   /* largest n of the gradient entry points */
 #define BED_VERSION 100 /* major*10000 + minor*100 + patch */
 
 typedef enum {
@@ -145,7 +144,6 @@ typedef enum {
  *   mode, degree, gap_floor   see above; degree in 0..64 (BED_GRAD_TAYLOR), gap_floor finite
  *                    and >= 0 (BED_GRAD_EXACT); the unused one is ignored
  *   grad_A           device, [batch][n][n] row-major fp32; may alias none of the inputs
- *   n                1 .. BED_MAX_N_GRAD (BED_ERR_N beyond)
  */
 int bed_syevd_backward(const float* evals, const float* evecs, const float* grad_evals,
                        const float* grad_evecs, int batch, int n, int mode, int degree,
@@ -167,7 +165,6 @@ int bed_syevd_backward(const float* evals, const float* evecs, const float* grad
  *   grad_out       device, const, [batch][n][n] (need not be symmetric)
  *   fn, floor      as in bed_spd_fn
  *   grad_A         device, [batch][n][n]; may alias none of the inputs
- *   n              1 .. BED_MAX_N_GRAD (BED_ERR_N beyond)
  */
 int bed_spd_fn_backward(const float* evals, const float* evecs, const float* grad_out, int batch,
                         int n, int fn, float floor, float* grad_A, void* stream);

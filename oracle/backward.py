@@ -84,11 +84,9 @@ def syevd_backward(lam, V, g_lam, g_V, mode=MODE_EXACT, gap_floor=0.0, degree=9,
     return V @ M @ np.swapaxes(V, -1, -2)
 
 
-def spd_fn_backward(lam, V, G, fn, floor):
-    """Gradient of <G, V f(max(Lambda, floor)) V^T> with respect to A (symmetric)."""
-    lam = np.asarray(lam, dtype=np.float64)
-    V = np.asarray(V, dtype=np.float64)
-    G = np.asarray(G, dtype=np.float64)
+def divided_differences(lam: np.ndarray, fn: int, floor: float) -> np.ndarray:
+    """Phi_ij = (f~(l_i) - f~(l_j)) / (l_i - l_j) with f~(x) = f(max(x, floor)); where the two
+    eigenvalues coincide (and on the diagonal) the derivative of f~."""
     a = np.maximum(lam, floor)
     clamped = lam < floor
     if fn == FN_SQRT:
@@ -103,10 +101,17 @@ def spd_fn_backward(lam, V, G, fn, floor):
     fp = np.where(clamped, 0.0, fp)                      # the clamped function is constant below the floor
     dl = lam[..., :, None] - lam[..., None, :]
     df = f[..., :, None] - f[..., None, :]
-    n = lam.shape[-1]
     same = dl == 0
     Phi = np.where(same, 0.0, df / np.where(same, 1.0, dl))
     # equal eigenvalues (and the diagonal): the derivative
-    Phi = np.where(same, 0.5 * (fp[..., :, None] + fp[..., None, :]), Phi)
+    return np.where(same, 0.5 * (fp[..., :, None] + fp[..., None, :]), Phi)
+
+
+def spd_fn_backward(lam, V, G, fn, floor):
+    """Gradient of <G, V f(max(Lambda, floor)) V^T> with respect to A (symmetric)."""
+    lam = np.asarray(lam, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    G = np.asarray(G, dtype=np.float64)
+    Phi = divided_differences(lam, fn, floor)
     C = np.swapaxes(V, -1, -2) @ (0.5 * (G + np.swapaxes(G, -1, -2))) @ V
     return V @ (Phi * C) @ np.swapaxes(V, -1, -2)

@@ -131,7 +131,6 @@ int bed_syevd_backward(const float* evals, const float* evecs, const float* grad
                        int batch, int n, int mode, int degree, float gap_floor, float* grad_A, void* stream) {
     int st = check_common(batch, n);
     if (st != BED_OK) return st;
-    if (n > BED_MAX_N_GRAD) return BED_ERR_N;
     if (mode != BED_GRAD_EXACT && mode != BED_GRAD_TAYLOR) return BED_ERR_ARG;
     if (mode == BED_GRAD_TAYLOR && (degree < 0 || degree > 64)) return BED_ERR_ARG;
     if (mode == BED_GRAD_EXACT && (!(gap_floor >= 0.f) || !(gap_floor < __builtin_inff()))) return BED_ERR_ARG;
@@ -162,7 +161,6 @@ int bed_spd_fn_backward(const float* evals, const float* evecs, const float* gra
                         float floor, float* grad_A, void* stream) {
     int st = check_common(batch, n);
     if (st != BED_OK) return st;
-    if (n > BED_MAX_N_GRAD) return BED_ERR_N;
     if (fn != BED_FN_SQRT && fn != BED_FN_INV_SQRT) return BED_ERR_ARG;
     if (!(floor >= 0.f) || !(floor < __builtin_inff())) return BED_ERR_ARG;
     if (fn == BED_FN_INV_SQRT && !(floor > 0.f)) return BED_ERR_ARG;

@@ -10,7 +10,8 @@
 // differences of f in place of K:
 //   g_A = V ( Phi o (V^T sym(G) V) ) V^T.
 //
-// One wavefront owns one matrix.  The three (four) n x n x n products are dense
+// One wavefront owns one matrix (four wavefronts, one row block of 32 each, for n > 64).
+// The three (four) n x n x n products are dense
 // contractions and run on v_mfma_f32_32x32x2_f32 (full fp32 operands and
 // accumulation); operands are staged in LDS with an odd row stride so that row
 // and column (transposed) operand reads are both conflict-free, and every
@@ -35,45 +36,51 @@ __device__ __forceinline__ void wave_sync() { __builtin_amdgcn_wave_barrier(); }
 //   D: register v (0..15) of lane l holds D[8 * (v / 4) + 4 * (l / 32) + v % 4][l % 32]
 __device__ __forceinline__ int acc_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
 
-// acc[ti][tj] = sum_k X[i][k] * Y[k][j] over k < kdim (kdim even), tiles of 32x32.
+// acc[tr][tj] = sum_k X[i][k] * Y[k][j] over k < kdim (kdim even), tiles of 32x32; the
+// wavefront computes the TR row tiles that start at tile row0.
 // XT / YT: the operand is stored transposed in its LDS buffer.
-template <int NT, bool XT, bool YT>
-__device__ __forceinline__ void product(floatx16 (&acc)[NT][NT], const float* X, const float* Y, int kdim, int lane) {
+template <int NT, int TR, bool XT, bool YT>
+__device__ __forceinline__ void product(floatx16 (&acc)[TR][NT], const float* X, const float* Y, int kdim, int lane,
+                                        int row0) {
     constexpr int LD = 32 * NT + 1;
     const int lo = lane & 31, hi = lane >> 5;
 #pragma unroll
-    for (int ti = 0; ti < NT; ++ti)
+    for (int ti = 0; ti < TR; ++ti)
 #pragma unroll
         for (int tj = 0; tj < NT; ++tj)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[ti][tj][v] = 0.f;
     for (int k0 = 0; k0 < kdim; k0 += 2) {
         const int k = k0 + hi;
-        float a[NT], b[NT];
+        float a[TR], b[NT];
+#pragma unroll
+        for (int t = 0; t < TR; ++t) {
+            const int r = 32 * (row0 + t) + lo;
+            a[t] = XT ? X[k * LD + r] : X[r * LD + k];
+        }
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             const int r = 32 * t + lo;
-            a[t] = XT ? X[k * LD + r] : X[r * LD + k];
             b[t] = YT ? Y[r * LD + k] : Y[k * LD + r];
         }
 #pragma unroll
-        for (int ti = 0; ti < NT; ++ti)
+        for (int ti = 0; ti < TR; ++ti)
 #pragma unroll
             for (int tj = 0; tj < NT; ++tj)
                 acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ti], b[tj], acc[ti][tj], 0, 0, 0);
     }
 }
 
-template <int NT>
-__device__ __forceinline__ void spill_to_lds(const floatx16 (&acc)[NT][NT], float* dst, int lane) {
+template <int NT, int TR>
+__device__ __forceinline__ void spill_to_lds(const floatx16 (&acc)[TR][NT], float* dst, int lane, int row0) {
     constexpr int LD = 32 * NT + 1;
 #pragma unroll
-    for (int ti = 0; ti < NT; ++ti)
+    for (int ti = 0; ti < TR; ++ti)
 #pragma unroll
         for (int tj = 0; tj < NT; ++tj)
 #pragma unroll
             for (int v = 0; v < 16; ++v)
-                dst[(32 * ti + acc_row(v, lane)) * LD + 32 * tj + (lane & 31)] = acc[ti][tj][v];
+                dst[(32 * (row0 + ti) + acc_row(v, lane)) * LD + 32 * tj + (lane & 31)] = acc[ti][tj][v];
 }
 
 // Coupling of the pair (a, b) = (lambda_i, lambda_j), i != j.
@@ -109,94 +116,106 @@ __device__ __forceinline__ float divided_difference(float li, float lj, int mode
     return phi;
 }
 
-template <int NT>
-__global__ __launch_bounds__(64) void grad_kernel(GradArgs args) {
+// NT tiles of 32 per side (1: n <= 32, 2: n <= 64, 4: n <= 128); NWV wavefronts per matrix,
+// each owning NT / NWV row tiles of every product.
+template <int NT, int NWV>
+__global__ __launch_bounds__(64 * NWV) void grad_kernel(GradArgs args) {
     constexpr int NP = 32 * NT;
     constexpr int LD = NP + 1;
+    constexpr int TR = NT / NWV;
+    constexpr int NTH = 64 * NWV;
     __shared__ float sV[NP * LD];      // V, row-major, zero padded
     __shared__ float sW[NP * LD];      // G, then the intermediate products
     __shared__ float sL[NP];           // eigenvalues
     __shared__ float sGl[NP];          // upstream gradient of the eigenvalues
 
-    const int lane = threadIdx.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int row0 = (NWV == 1) ? 0 : (tid >> 6) * TR;     // first row tile of this wavefront
     const int b = blockIdx.x;
     const int n = args.n;
     const int kdim = (n + 1) & ~1;
     const bool ed = (args.mode == kGradExact || args.mode == kGradTaylor);
+    // LDS written by one wavefront and read by another needs a workgroup barrier
+    auto sync = [&]() {
+        if (NWV == 1) wave_sync();
+        else __syncthreads();
+    };
 
-    for (int idx = lane; idx < NP * LD; idx += 64) {
+    for (int idx = tid; idx < NP * LD; idx += NTH) {
         sV[idx] = 0.f;
         sW[idx] = 0.f;
     }
-    if (lane < NP) {
-        sL[lane] = (lane < n) ? args.evals[(size_t)b * n + lane] : 0.f;
-        sGl[lane] = (lane < n && args.g_evals) ? args.g_evals[(size_t)b * n + lane] : 0.f;
+    if (tid < NP) {
+        sL[tid] = (tid < n) ? args.evals[(size_t)b * n + tid] : 0.f;
+        sGl[tid] = (tid < n && args.g_evals) ? args.g_evals[(size_t)b * n + tid] : 0.f;
     }
-    wave_sync();
+    sync();
     {
         const float* __restrict__ Vb = args.evecs + (size_t)b * n * n;
         const float* __restrict__ Gb = args.g_mat ? args.g_mat + (size_t)b * n * n : nullptr;
         const float rcp_n = 1.0f / (float)n;
-        for (int idx = lane; idx < n * n; idx += 64) {
+        for (int idx = tid; idx < n * n; idx += NTH) {
             const int i = (int)(((float)idx + 0.5f) * rcp_n);
             const int j = idx - i * n;
             sV[i * LD + j] = Vb[idx];
             if (Gb) sW[i * LD + j] = Gb[idx];
         }
     }
-    wave_sync();
+    sync();
 
-    floatx16 acc[NT][NT];
+    floatx16 acc[TR][NT];
     if (!ed) {
         // spectral function: T = G V first, so that C = V^T G V
-        product<NT, false, false>(acc, sW, sV, kdim, lane);
-        wave_sync();
-        spill_to_lds<NT>(acc, sW, lane);
-        wave_sync();
+        product<NT, TR, false, false>(acc, sW, sV, kdim, lane, row0);
+        sync();
+        spill_to_lds<NT, TR>(acc, sW, lane, row0);
+        sync();
     }
     // C = V^T T  (T = g_V for the eigendecomposition itself)
-    product<NT, true, false>(acc, sV, sW, kdim, lane);
-    wave_sync();
-    spill_to_lds<NT>(acc, sW, lane);
-    wave_sync();
+    product<NT, TR, true, false>(acc, sV, sW, kdim, lane, row0);
+    sync();
+    spill_to_lds<NT, TR>(acc, sW, lane, row0);
+    sync();
     // M: element (i, j) needs C_ij (own register), C_ji, lambda_i, lambda_j
 #pragma unroll
-    for (int ti = 0; ti < NT; ++ti)
+    for (int ti = 0; ti < TR; ++ti)
 #pragma unroll
         for (int tj = 0; tj < NT; ++tj)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int i = 32 * ti + acc_row(v, lane);
+                const int i = 32 * (row0 + ti) + acc_row(v, lane);
                 const int j = 32 * tj + (lane & 31);
                 const float cij = acc[ti][tj][v];
                 const float cji = sW[j * LD + i];
                 const float li = sL[i], lj = sL[j];
                 float m;
                 if (ed) {
-                    m = (i == j) ? sGl[i] : 0.5f * coupling(li, lj, j > i, args.mode, args.degree, args.param) * (cij - cji);
+                    m = (i == j) ? sGl[i]
+                                 : 0.5f * coupling(li, lj, j > i, args.mode, args.degree, args.param) * (cij - cji);
                 } else {
                     m = 0.5f * divided_difference(li, lj, args.mode, args.param) * (cij + cji);
                 }
                 acc[ti][tj][v] = (i < n && j < n) ? m : 0.f;
             }
-    wave_sync();
-    spill_to_lds<NT>(acc, sW, lane);
-    wave_sync();
+    sync();
+    spill_to_lds<NT, TR>(acc, sW, lane, row0);
+    sync();
     // U = V M
-    product<NT, false, false>(acc, sV, sW, kdim, lane);
-    wave_sync();
-    spill_to_lds<NT>(acc, sW, lane);
-    wave_sync();
+    product<NT, TR, false, false>(acc, sV, sW, kdim, lane, row0);
+    sync();
+    spill_to_lds<NT, TR>(acc, sW, lane, row0);
+    sync();
     // g_A = U V^T
-    product<NT, false, true>(acc, sW, sV, kdim, lane);
+    product<NT, TR, false, true>(acc, sW, sV, kdim, lane, row0);
     float* __restrict__ Ob = args.g_A + (size_t)b * n * n;
 #pragma unroll
-    for (int ti = 0; ti < NT; ++ti)
+    for (int ti = 0; ti < TR; ++ti)
 #pragma unroll
         for (int tj = 0; tj < NT; ++tj)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int i = 32 * ti + acc_row(v, lane);
+                const int i = 32 * (row0 + ti) + acc_row(v, lane);
                 const int j = 32 * tj + (lane & 31);
                 if (i < n && j < n) Ob[i * n + j] = acc[ti][tj][v];
             }
@@ -207,9 +226,11 @@ __global__ __launch_bounds__(64) void grad_kernel(GradArgs args) {
 hipError_t launch_grad(const GradArgs& args, hipStream_t stream) {
     if (args.batch == 0) return hipSuccess;
     if (args.n <= 32)
-        hipLaunchKernelGGL(grad_kernel<1>, dim3(args.batch), dim3(64), 0, stream, args);
+        hipLaunchKernelGGL((grad_kernel<1, 1>), dim3(args.batch), dim3(64), 0, stream, args);
+    else if (args.n <= 64)
+        hipLaunchKernelGGL((grad_kernel<2, 1>), dim3(args.batch), dim3(64), 0, stream, args);
     else
-        hipLaunchKernelGGL(grad_kernel<2>, dim3(args.batch), dim3(64), 0, stream, args);
+        hipLaunchKernelGGL((grad_kernel<4, 4>), dim3(args.batch), dim3(256), 0, stream, args);
     return hipGetLastError();
 }
 

@@ -523,9 +523,10 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
 template <int N, bool WANT_V, int STAGE>
 __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
     constexpr int W = lanes_for(N);
-    // When the rows fit in half a wavefront (N <= 32), lanes 32..63 shadow rows 0..31 from
-    // load to store: both halves hold the same row data, and in the QR phase they carry the
-    // two sweeps of an iteration.
+    // When the rows fit in half a wavefront (N <= 32), lane 32 + r works on the same row r as
+    // lane r from load to store: in the tridiagonalisation the upper half holds the rows of P
+    // (the lower half those of A), in the QR phase the halves carry the two sweeps of an
+    // iteration.
     constexpr bool HALF = (N <= 32);
     // Column stride: odd (conflict-free rows and columns) and wide enough that every lane
     // owns a row slot, so no V access needs a lane predicate (rows >= n are idle lanes).

@@ -118,10 +118,14 @@ def test_spectral_function(fn):
     check_fn(workloads.covariance(3, 128, 300, 1e-2, 781), fn, 1e-6, "wishart n=128")
 
 
-def test_gradients_are_limited_to_n_64():
-    import torch
-    from paper_2207_04228_amd import binding
-    lam = torch.zeros((1, 65), device="cuda:0")
-    V = torch.zeros((1, 65, 65), device="cuda:0")
-    with pytest.raises(binding.BedError):
-        binding.bed_syevd_backward(lam, V, lam, None)
+def test_gradients():
+    from test_gpu_backward import _check_ed, _check_fn
+    from paper_2207_04228_amd import workloads
+    for n in (65, 100, 128):
+        A = workloads.covariance(5, n, 4 * n, 1e-3, 782 + n)
+        _check_ed(A, 0, f"wishart n={n}", gap_floor=1e-5, seed=n)
+        _check_ed(A, 1, f"wishart n={n}", degree=9, seed=n)
+        _check_fn(A, 0, 1e-6, f"wishart n={n}", seed=n)
+        _check_fn(A, 1, 1e-6, f"wishart n={n}", seed=n)
+    lam = workloads.clustered_spectrum(3, 96, 901)
+    _check_ed(workloads.from_spectrum(lam, seed=902), 1, "clustered n=96", degree=9, seed=3)

@@ -76,8 +76,8 @@ def test_argument_validation_is_host_side(lib):
     assert lib.bed_syevd_backward(L, V, L, None, 1, 4, 1, 65, f(0.0), O, None) == -7        # degree out of range
     assert lib.bed_syevd_backward(L, V, L, None, 1, 4, 0, 9, f(float("nan")), O, None) == -7
     assert lib.bed_syevd_backward(L, V, L, None, 1, 4, 0, 9, f(0.0), V, None) == -6         # output aliases evecs
-    assert lib.bed_syevd_backward(L, V, L, None, 1, 65, 0, 9, f(0.0), O, None) == -3         # gradients: n <= 64
-    assert lib.bed_spd_fn_backward(L, V, A, 1, 65, 0, f(0.0), O, None) == -3
+    assert lib.bed_syevd_backward(L, V, L, None, 1, 129, 0, 9, f(0.0), O, None) == -3
+    assert lib.bed_spd_fn_backward(L, V, A, 1, 129, 0, f(0.0), O, None) == -3
     assert lib.bed_syevd_backward(L, V, L, None, 0, 4, 0, 9, f(0.0), O, None) == 0
     assert lib.bed_spd_fn_backward(L, V, None, 1, 4, 0, f(0.0), O, None) == -1
     assert lib.bed_spd_fn_backward(L, V, A, 1, 4, 1, f(0.0), O, None) == -7                 # inverse sqrt, floor 0

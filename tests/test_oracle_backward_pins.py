@@ -149,8 +149,8 @@ _MUTATIONS = {
     "symmetrisation dropped": ("M = 0.5 * (M + np.swapaxes(M, -1, -2))", "M = M"),
     "g_V^T V instead of V^T g_V": ("C = np.swapaxes(V, -1, -2) @ np.asarray(g_V, dtype=np.float64)",
                                    "C = np.swapaxes(np.asarray(g_V, dtype=np.float64), -1, -2) @ V"),
-    "derivative on the diagonal dropped": ("Phi = np.where(same, 0.5 * (fp[..., :, None] + fp[..., None, :]), Phi)",
-                                           "Phi = Phi"),
+    "derivative on the diagonal dropped": ("return np.where(same, 0.5 * (fp[..., :, None] + fp[..., None, :]), Phi)",
+                                           "return Phi"),
     "series one term short": ("for k in range(degree + 1):", "for k in range(degree):"),
     "wrong sign of the inverse square root's derivative": ("fp = -0.5 * a ** -1.5", "fp = 0.5 * a ** -1.5"),
     "clamped eigenvalues keep their derivative": ("fp = np.where(clamped, 0.0, fp)", "fp = fp"),
