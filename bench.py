@@ -214,6 +214,37 @@ def main(argv=None) -> int:
             reps) * 1e6
         extras["spd_inv_sqrt_backward_us"][str(n)] = timed(
             lambda: binding.bed_spd_fn_backward(ev, V, gV, binding.BED_FN_INV_SQRT, 1e-6, grad_A=F), reps) * 1e6
+    if not a.no_extras:
+        # the four calls of a step recorded once into a HIP graph and replayed
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            step()
+        stream.wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        tg0 = time.perf_counter()
+        for _ in range(a.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        tg = (time.perf_counter() - tg0) / a.steps
+        extras["graph_replay"] = {"ms_per_step": tg * 1e3, "matrices_per_s": n_mats / tg}
+        # the four sizes on four streams (independent work; each call fills half of the SIMDs)
+        streams = [torch.cuda.Stream() for _ in bufs]
+        for st_ in streams:
+            st_.wait_stream(stream)
+        torch.cuda.synchronize()
+        tc0 = time.perf_counter()
+        for _ in range(a.steps):
+            for st_, (n, A, ev, V) in zip(streams, bufs):
+                binding.bed_syevd(A, ev, V, stream=st_)
+        torch.cuda.synchronize()
+        tcs = (time.perf_counter() - tc0) / a.steps
+        extras["four_streams"] = {"ms_per_step": tcs * 1e3, "matrices_per_s": n_mats / tcs}
     for n, batch in (() if a.no_extras else ((4, 65536), (8, 65536), (16, 4096), (32, 4096), (64, 256), (128, 256))):
         A32b = (workloads.config2(batch) if n == 4 else
                 workloads.config3(n, batch=batch) if n <= 32 else
