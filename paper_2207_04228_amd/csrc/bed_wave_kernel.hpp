@@ -608,11 +608,14 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
 #pragma unroll
                     for (int c = J + 1; c < N; ++c) pp[c & 3] = fmaf(x[c], u[c], pp[c & 3]);
                     const float pw = beta * ((pp[0] + pp[1]) + (pp[2] + pp[3]));     // p (A lanes), w (P lanes)
-                    const float K = 0.5f * beta * wave_sum<W>(ur * pw);
-                    const float q = fmaf(-K, ur, pw);         // q = p - K u; stays w in the P lanes (u = 0 there)
-                    sq[lane] = q;
+                    // A - q u^T - u q^T with q = p - K u, K = u^T p / |u|^2, regrouped as
+                    // A - (p - 2K u) u^T - u p^T: p can be broadcast before K is known, so the LDS
+                    // round trip runs under the reduction.
+                    sq[lane] = pw;
+                    const float K2 = beta * wave_sum<W>(ur * pw);                    // 2K
+                    const float sr = fmaf(-K2, ur, pw);       // p - 2K u; stays w in the P lanes (u = 0 there)
 #pragma unroll
-                    for (int c = J + 1; c < N; ++c) x[c] = fmaf(-q, u[c], x[c]);
+                    for (int c = J + 1; c < N; ++c) x[c] = fmaf(-sr, u[c], x[c]);
                     __syncthreads();
 #pragma unroll
                     for (int c = J + 1; c < N; ++c) x[c] = fmaf(-ur, sq[c], x[c]);
@@ -706,11 +709,13 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                     }
                     const float p = beta * ((pp[0] + pp[1]) + (pp[2] + pp[3]));
                     wd = beta * ((ww[0] + ww[1]) + (ww[2] + ww[3]));
-                    const float K = 0.5f * beta * wave_sum<W>(ur * p);
-                    const float q = fmaf(-K, ur, p);              // q = p - K u (symmetric rank-2 form)
-                    sq[lane] = q;
+                    // A - q u^T - u q^T with q = p - K u, regrouped as A - (p - 2K u) u^T - u p^T
+                    // (p is broadcast before K is known; same arithmetic as the role-lane variant)
+                    sq[lane] = p;
+                    const float K2 = beta * wave_sum<W>(ur * p);  // 2K
+                    const float sr = fmaf(-K2, ur, p);
 #pragma unroll
-                    for (int c = J + 1; c < N; ++c) a[c] = fmaf(-q, u[c], a[c]);
+                    for (int c = J + 1; c < N; ++c) a[c] = fmaf(-sr, u[c], a[c]);
                     __syncthreads();
 #pragma unroll
                     for (int c = J + 1; c < N; ++c) {
