@@ -118,8 +118,13 @@ __device__ __forceinline__ float divided_difference(float li, float lj, int mode
 
 // NT tiles of 32 per side (1: n <= 32, 2: n <= 64, 4: n <= 128); NWV wavefronts per matrix,
 // each owning NT / NWV row tiles of every product.
-template <int NT, int NWV>
+// PB > 0 (n <= PB <= 16, NT = NWV = 1): 32 / PB matrices share the wavefront as the diagonal
+// blocks of one 32 x 32 operand; products of block-diagonal matrices are block diagonal, so
+// the same instruction stream serves all of them.
+template <int NT, int NWV, int PB>
 __global__ __launch_bounds__(64 * NWV) void grad_kernel(GradArgs args) {
+    static_assert(PB == 0 || (NT == 1 && NWV == 1 && 32 % PB == 0), "packing needs one 32 x 32 tile");
+    constexpr int NMAT = PB ? 32 / PB : 1;       // matrices per workgroup
     constexpr int NP = 32 * NT;
     constexpr int LD = NP + 1;
     constexpr int TR = NT / NWV;
@@ -132,10 +137,14 @@ __global__ __launch_bounds__(64 * NWV) void grad_kernel(GradArgs args) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int row0 = (NWV == 1) ? 0 : (tid >> 6) * TR;     // first row tile of this wavefront
-    const int b = blockIdx.x;
+    const int b = blockIdx.x * NMAT;           // first matrix of this workgroup
+    const int count = min(NMAT, args.batch - b);
     const int n = args.n;
-    const int kdim = (n + 1) & ~1;
+    const int kdim = PB ? 32 : ((n + 1) & ~1);
     const bool ed = (args.mode == kGradExact || args.mode == kGradTaylor);
+    // position p of the (padded) operand -> matrix p / PB, local index p % PB
+    auto blk = [](int p) { return PB ? p / (PB ? PB : 1) : 0; };
+    auto loc = [](int p) { return PB ? p % (PB ? PB : 1) : p; };
     // LDS written by one wavefront and read by another needs a workgroup barrier
     auto sync = [&]() {
         if (NWV == 1) wave_sync();
@@ -147,19 +156,26 @@ __global__ __launch_bounds__(64 * NWV) void grad_kernel(GradArgs args) {
         sW[idx] = 0.f;
     }
     if (tid < NP) {
-        sL[tid] = (tid < n) ? args.evals[(size_t)b * n + tid] : 0.f;
-        sGl[tid] = (tid < n && args.g_evals) ? args.g_evals[(size_t)b * n + tid] : 0.f;
+        const bool ok = blk(tid) < count && loc(tid) < n;
+        const size_t at = (size_t)(b + blk(tid)) * n + loc(tid);
+        sL[tid] = ok ? args.evals[at] : 0.f;
+        sGl[tid] = (ok && args.g_evals) ? args.g_evals[at] : 0.f;
     }
     sync();
     {
+        // the workgroup's matrices are contiguous in memory: one coalesced pass over all of them
         const float* __restrict__ Vb = args.evecs + (size_t)b * n * n;
         const float* __restrict__ Gb = args.g_mat ? args.g_mat + (size_t)b * n * n : nullptr;
         const float rcp_n = 1.0f / (float)n;
-        for (int idx = tid; idx < n * n; idx += NTH) {
-            const int i = (int)(((float)idx + 0.5f) * rcp_n);
-            const int j = idx - i * n;
-            sV[i * LD + j] = Vb[idx];
-            if (Gb) sW[i * LD + j] = Gb[idx];
+        const float rcp_nn = rcp_n * rcp_n;
+        for (int idx = tid; idx < count * n * n; idx += NTH) {
+            const int m = PB ? (int)(((float)idx + 0.5f) * rcp_nn) : 0;
+            const int r = idx - m * n * n;
+            const int i = (int)(((float)r + 0.5f) * rcp_n);
+            const int j = r - i * n;
+            const int at = (m * PB + i) * LD + m * PB + j;
+            sV[at] = Vb[idx];
+            if (Gb) sW[at] = Gb[idx];
         }
     }
     sync();
@@ -196,7 +212,8 @@ __global__ __launch_bounds__(64 * NWV) void grad_kernel(GradArgs args) {
                 } else {
                     m = 0.5f * divided_difference(li, lj, args.mode, args.param) * (cij + cji);
                 }
-                acc[ti][tj][v] = (i < n && j < n) ? m : 0.f;
+                const bool inside = blk(i) == blk(j) && blk(i) < count && loc(i) < n && loc(j) < n;
+                acc[ti][tj][v] = inside ? m : 0.f;
             }
     sync();
     spill_to_lds<NT, TR>(acc, sW, lane, row0);
@@ -217,7 +234,8 @@ __global__ __launch_bounds__(64 * NWV) void grad_kernel(GradArgs args) {
             for (int v = 0; v < 16; ++v) {
                 const int i = 32 * (row0 + ti) + acc_row(v, lane);
                 const int j = 32 * tj + (lane & 31);
-                if (i < n && j < n) Ob[i * n + j] = acc[ti][tj][v];
+                const bool inside = blk(i) == blk(j) && blk(i) < count && loc(i) < n && loc(j) < n;
+                if (inside) Ob[(size_t)blk(i) * n * n + loc(i) * n + loc(j)] = acc[ti][tj][v];
             }
 }
 
@@ -225,12 +243,19 @@ __global__ __launch_bounds__(64 * NWV) void grad_kernel(GradArgs args) {
 
 hipError_t launch_grad(const GradArgs& args, hipStream_t stream) {
     if (args.batch == 0) return hipSuccess;
-    if (args.n <= 32)
-        hipLaunchKernelGGL((grad_kernel<1, 1>), dim3(args.batch), dim3(64), 0, stream, args);
-    else if (args.n <= 64)
-        hipLaunchKernelGGL((grad_kernel<2, 1>), dim3(args.batch), dim3(64), 0, stream, args);
+    const int n = args.n, B = args.batch;
+    if (n <= 4)
+        hipLaunchKernelGGL((grad_kernel<1, 1, 4>), dim3((B + 7) / 8), dim3(64), 0, stream, args);
+    else if (n <= 8)
+        hipLaunchKernelGGL((grad_kernel<1, 1, 8>), dim3((B + 3) / 4), dim3(64), 0, stream, args);
+    else if (n <= 16)
+        hipLaunchKernelGGL((grad_kernel<1, 1, 16>), dim3((B + 1) / 2), dim3(64), 0, stream, args);
+    else if (n <= 32)
+        hipLaunchKernelGGL((grad_kernel<1, 1, 0>), dim3(B), dim3(64), 0, stream, args);
+    else if (n <= 64)
+        hipLaunchKernelGGL((grad_kernel<2, 1, 0>), dim3(B), dim3(64), 0, stream, args);
     else
-        hipLaunchKernelGGL((grad_kernel<4, 4>), dim3(args.batch), dim3(256), 0, stream, args);
+        hipLaunchKernelGGL((grad_kernel<4, 4, 0>), dim3(B), dim3(256), 0, stream, args);
     return hipGetLastError();
 }
 
