@@ -296,7 +296,17 @@ def main(argv=None) -> int:
                     res32 = (lam, Vo)
             tc1 = time.perf_counter()
             best = (tc1 - tc0) if best is None else min(best, tc1 - tc0)
+        # context: the same oracle on one thread, and the host LAPACK (float32 eigh) on the same inputs
+        t1a = time.perf_counter()
+        for n, A32 in points:
+            jacobi.syevd(A32, threads=1)
+        t1b = time.perf_counter()
+        for n, A32 in points:
+            np.linalg.eigh(A32)
+        t1c = time.perf_counter()
         cpu_baseline = {
+            "single_thread_value": n_mats / (t1b - t1a),
+            "lapack_eigh_f32_value": n_mats / (t1c - t1b),
             "value": n_mats / best,
             "unit": "matrices/s",
             "cores": int(used),
