@@ -245,6 +245,14 @@ def main(argv=None) -> int:
         torch.cuda.synchronize()
         tcs = (time.perf_counter() - tc0) / a.steps
         extras["four_streams"] = {"ms_per_step": tcs * 1e3, "matrices_per_s": n_mats / tcs}
+    if not a.no_extras:
+        # the mini-batch shapes of the paper's application tables (Tables 2-4), one call each
+        extras["paper_shapes_us"] = {}
+        for batch, n in ((16, 4), (8, 8), (4, 16), (768, 32), (768, 36), (256, 4), (128, 8), (64, 16)):
+            Ap = torch.from_numpy(workloads.covariance(batch, n, 4 * n, 1e-4, 31 + n)).to(dev)
+            evp = torch.empty((batch, n), dtype=torch.float32, device=dev)
+            Vp = torch.empty((batch, n, n), dtype=torch.float32, device=dev)
+            extras["paper_shapes_us"][f"{batch}x{n}x{n}"] = timed(lambda: binding.bed_syevd(Ap, evp, Vp), 20) * 1e6
     for n, batch in (() if a.no_extras else ((4, 65536), (8, 65536), (16, 4096), (32, 4096), (64, 256), (128, 256))):
         A32b = (workloads.config2(batch) if n == 4 else
                 workloads.config3(n, batch=batch) if n <= 32 else
