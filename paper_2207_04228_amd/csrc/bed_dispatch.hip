@@ -9,7 +9,9 @@ hipError_t launch_wave_n8(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n16(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n24(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n32(const KernelArgs&, int, bool, hipStream_t);
+hipError_t launch_wave_n40(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n48(const KernelArgs&, int, bool, hipStream_t);
+hipError_t launch_wave_n56(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n64(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_block(const KernelArgs&, int, bool, hipStream_t);
 
@@ -26,7 +28,9 @@ hipError_t launch(const KernelArgs& args, int stage, bool want_v, hipStream_t st
     if (n <= 16) return launch_wave_n16(args, stage, want_v, stream);
     if (n <= 24) return launch_wave_n24(args, stage, want_v, stream);
     if (n <= 32) return launch_wave_n32(args, stage, want_v, stream);
+    if (n <= 40) return launch_wave_n40(args, stage, want_v, stream);
     if (n <= 48) return launch_wave_n48(args, stage, want_v, stream);
+    if (n <= 56) return launch_wave_n56(args, stage, want_v, stream);
     if (n <= 64) return launch_wave_n64(args, stage, want_v, stream);
     return launch_block(args, stage, want_v, stream);     // 64 < n <= 128: four wavefronts per matrix
 }
