@@ -599,26 +599,22 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                     ur = active ? ur : 0.f;
                     const float beta = active ? __builtin_amdgcn_rcpf(fmaf(fabsf(x0), nrm, alpha)) : 0.f;  // 2/|u|^2
                     eJ = active ? -sigma : x0;
-                    svec[lane] = ur;                          // entries 32..63 (P lanes) are zero and never read
-                    __syncthreads();
+                    // u and p are broadcast with v_readlane (the entries live in lanes 0..31; the
+                    // results are scalars that the FMAs take as operands): no LDS round trip and no
+                    // barrier in the whole reduction
                     float u[N];
 #pragma unroll
-                    for (int c = J + 1; c < N; ++c) u[c] = svec[c];
+                    for (int c = J + 1; c < N; ++c) u[c] = read_lane(ur, c);
                     float pp[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int c = J + 1; c < N; ++c) pp[c & 3] = fmaf(x[c], u[c], pp[c & 3]);
                     const float pw = beta * ((pp[0] + pp[1]) + (pp[2] + pp[3]));     // p (A lanes), w (P lanes)
                     // A - q u^T - u q^T with q = p - K u, K = u^T p / |u|^2, regrouped as
-                    // A - (p - 2K u) u^T - u p^T: p can be broadcast before K is known, so the LDS
-                    // round trip runs under the reduction.
-                    sq[lane] = pw;
+                    // A - (p - 2K u) u^T - u p^T: the broadcast of p does not wait for K.
                     const float K2 = beta * wave_sum<W>(ur * pw);                    // 2K
                     const float sr = fmaf(-K2, ur, pw);       // p - 2K u; stays w in the P lanes (u = 0 there)
 #pragma unroll
-                    for (int c = J + 1; c < N; ++c) x[c] = fmaf(-sr, u[c], x[c]);
-                    __syncthreads();
-#pragma unroll
-                    for (int c = J + 1; c < N; ++c) x[c] = fmaf(-ur, sq[c], x[c]);
+                    for (int c = J + 1; c < N; ++c) x[c] = fmaf(-ur, read_lane(pw, c), fmaf(-sr, u[c], x[c]));
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -690,16 +686,19 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                     ur = active ? ur : 0.f;
                     const float beta = active ? __builtin_amdgcn_rcpf(fmaf(fabsf(x0), nrm, alpha)) : 0.f;  // 2/|u|^2
                     eJ = active ? -sigma : x0;
-                    svec[lane] = ur;
+                    // Up to 32 rows, u and p are broadcast with v_readlane (scalar operands of the
+                    // FMAs); beyond, through LDS (one write, then 128-bit reads of one address).
+                    constexpr bool RL = (N <= 32);
+                    if (!RL) svec[lane] = ur;
                     if (WANT_V && J > 0) {
                         // deferred: V <- V - w u^T of step J-1 (columns J .. N-1)
 #pragma unroll
                         for (int c = J; c < N; ++c) v[c] = fmaf(-wd, ud[c], v[c]);
                     }
-                    __syncthreads();
+                    if (!RL) __syncthreads();
                     float u[N];
 #pragma unroll
-                    for (int c = J + 1; c < N; ++c) u[c] = svec[c];
+                    for (int c = J + 1; c < N; ++c) u[c] = RL ? read_lane(ur, c) : svec[c];
                     // p = 2 A u / |u|^2, w = 2 V u / |u|^2; four partial sums each
                     float pp[4] = {0.f, 0.f, 0.f, 0.f}, ww[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -711,15 +710,15 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
                     wd = beta * ((ww[0] + ww[1]) + (ww[2] + ww[3]));
                     // A - q u^T - u q^T with q = p - K u, regrouped as A - (p - 2K u) u^T - u p^T
                     // (p is broadcast before K is known; same arithmetic as the role-lane variant)
-                    sq[lane] = p;
+                    if (!RL) sq[lane] = p;
                     const float K2 = beta * wave_sum<W>(ur * p);  // 2K
                     const float sr = fmaf(-K2, ur, p);
 #pragma unroll
                     for (int c = J + 1; c < N; ++c) a[c] = fmaf(-sr, u[c], a[c]);
-                    __syncthreads();
+                    if (!RL) __syncthreads();
 #pragma unroll
                     for (int c = J + 1; c < N; ++c) {
-                        a[c] = fmaf(-ur, sq[c], a[c]);
+                        a[c] = fmaf(-ur, RL ? read_lane(p, c) : sq[c], a[c]);
                         ud[c] = u[c];
                     }
                     // keep the steps apart: interleaving them makes the compiler hoist the next
