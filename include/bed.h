@@ -24,7 +24,7 @@ extern "C" {
 #endif
 
 #define BED_MAX_N 128
-#define BED_VERSION 100 /* major*10000 + minor*100 + patch */
+#define BED_VERSION 300 /* major*10000 + minor*100 + patch: 0.3.0 (spectral function, gradients, n <= 128) */
 
 typedef enum {
     BED_OK = 0,

@@ -35,7 +35,7 @@ def test_header_symbols_are_exported(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert binding.bed_version() == 100
+    assert binding.bed_version() == 300
     assert binding.bed_status_string(0) == "BED_OK"
     for code in (-1, -2, -3, -4, -5, -6, -7):
         assert binding.bed_status_string(code).startswith("BED_ERR_")
