@@ -21,7 +21,7 @@ hipError_t launch(const KernelArgs& args, int stage, bool want_v, hipStream_t st
     // Tiny matrices in very large batches: one matrix per lane (64 per wavefront).  Below these
     // batch sizes the chip is not full and the one-wavefront-per-matrix kernels, whose
     // per-matrix latency is much lower, finish first (measured crossovers on MI355X).
-    if (stage == kFull && ((n <= 4 && args.batch >= 8192) || (n <= 8 && args.batch >= 16384)))
+    if (stage == kFull && ((n <= 4 && args.batch >= 6144) || (n <= 8 && args.batch >= 12288)))
         return launch_lane(args, want_v, stream);
     if (n <= 4) return launch_wave_n4(args, stage, want_v, stream);
     if (n <= 8) return launch_wave_n8(args, stage, want_v, stream);
