@@ -6,8 +6,11 @@ namespace bed {
 hipError_t launch_lane(const KernelArgs&, bool, hipStream_t);
 hipError_t launch_wave_n4(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n8(const KernelArgs&, int, bool, hipStream_t);
+hipError_t launch_wave_n12(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n16(const KernelArgs&, int, bool, hipStream_t);
+hipError_t launch_wave_n20(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n24(const KernelArgs&, int, bool, hipStream_t);
+hipError_t launch_wave_n28(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n32(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n40(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n48(const KernelArgs&, int, bool, hipStream_t);
@@ -25,8 +28,11 @@ hipError_t launch(const KernelArgs& args, int stage, bool want_v, hipStream_t st
         return launch_lane(args, want_v, stream);
     if (n <= 4) return launch_wave_n4(args, stage, want_v, stream);
     if (n <= 8) return launch_wave_n8(args, stage, want_v, stream);
+    if (n <= 12) return launch_wave_n12(args, stage, want_v, stream);
     if (n <= 16) return launch_wave_n16(args, stage, want_v, stream);
+    if (n <= 20) return launch_wave_n20(args, stage, want_v, stream);
     if (n <= 24) return launch_wave_n24(args, stage, want_v, stream);
+    if (n <= 28) return launch_wave_n28(args, stage, want_v, stream);
     if (n <= 32) return launch_wave_n32(args, stage, want_v, stream);
     if (n <= 40) return launch_wave_n40(args, stage, want_v, stream);
     if (n <= 48) return launch_wave_n48(args, stage, want_v, stream);

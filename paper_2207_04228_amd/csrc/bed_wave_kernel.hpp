@@ -514,7 +514,7 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
 }
 
 // ---------------------------------------------------------------------------
-// N      register-array size (4, 8, 16, 24, 32, 40, 48, 56, 64); n <= N at run time
+// N      register-array size (4, 8, 12, 16, 20, 24, 28, 32, 40, 48, 56, 64); n <= N at run time
 // WANT_V accumulate eigenvectors
 // STAGE  kFull, kTridiagOnly (stage hook 1), kQrOnly (stage hook 2)
 // Shifts: both eigenvalues of the trailing 2x2 block of the active window are taken
