@@ -99,6 +99,25 @@ int bed_tridiag_qr(const float* d, const float* e, int batch, int n,
                    void* stream);
 
 /*
+ * Stage hook 3 -- a given number of shifted QR sweeps on a given symmetric tridiagonal
+ * matrix, result left as it stands (Sec. 3.2.1, 3.2.2): one outer iteration is two sweeps
+ * over the active window, the first with the eigenvalue of the trailing 2x2 block that is
+ * closer to the last diagonal entry, the second with the other one, both taken from the
+ * matrix as it was before the first sweep (Eq. (15), App. A.3).  Exists so that a test can
+ * compare one iteration with T' = R Q + mu I of an explicit QR factorisation.
+ *   d, e        as bed_tridiag_qr
+ *   sweeps      >= 1: iterations run while fewer than this many sweeps have been done
+ *               (2 = exactly one outer iteration on a matrix with no negligible entry)
+ *   d_out,e_out device, [batch][n]: the tridiagonal after those sweeps (not sorted)
+ *   Q           device, [batch][n][n] row-major: the product of the rotations, T_out = Q^T T Q
+ *   rotations   device, [batch] or NULL
+ *   n           1 .. 64 (BED_ERR_N beyond)
+ */
+int bed_tridiag_qr_sweeps(const float* d, const float* e, int batch, int n, int sweeps,
+                          float* d_out, float* e_out, float* Q, unsigned* rotations,
+                          void* stream);
+
+/*
  * Fused spectral function of a batch of symmetric positive (semi-)definite
  * matrices: out_b = V_b f(max(Lambda_b, floor)) V_b^T, computed from the
  * eigendecomposition inside the same launch, without writing V.  This is what

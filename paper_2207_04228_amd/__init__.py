@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     bed_syevd_info,
     bed_tridiag,
     bed_tridiag_qr,
+    bed_tridiag_qr_sweeps,
     bed_version,
     bed_status_string,
     library_path,

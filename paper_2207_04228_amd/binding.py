@@ -45,6 +45,8 @@ def load_library():
         lib.bed_tridiag.restype = ci
         lib.bed_tridiag_qr.argtypes = [vp, vp, ci, ci, vp, vp, vp, vp, vp]
         lib.bed_tridiag_qr.restype = ci
+        lib.bed_tridiag_qr_sweeps.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp, vp]
+        lib.bed_tridiag_qr_sweeps.restype = ci
         lib.bed_spd_fn.argtypes = [vp, ci, ci, ci, ctypes.c_float, vp, vp, vp, vp]
         lib.bed_spd_fn.restype = ci
         lib.bed_syevd_backward.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ctypes.c_float, vp, vp]
@@ -163,6 +165,25 @@ def bed_tridiag_qr(d, e, *, want_vectors=True, stream=None):
     if st != 0:
         raise BedError(st, "bed_tridiag_qr")
     return evals, evecs, info, rot
+
+
+def bed_tridiag_qr_sweeps(d, e, sweeps, *, stream=None):
+    """At most `sweeps` shifted QR sweeps on tridiagonal (d, e).  Returns (d_out, e_out, Q, rotations)."""
+    import torch
+    _check_dev(d, "d", torch.float32)
+    _check_dev(e, "e", torch.float32)
+    batch, n = d.shape
+    if tuple(e.shape) != (batch, n):
+        raise ValueError("e must be [batch, n] (last entry of each row ignored)")
+    d_out = torch.empty_like(d)
+    e_out = torch.empty_like(e)
+    Q = torch.empty((batch, n, n), dtype=torch.float32, device=d.device)
+    rot = torch.empty((batch,), dtype=torch.int32, device=d.device)
+    st = load_library().bed_tridiag_qr_sweeps(_ptr(d), _ptr(e), batch, n, int(sweeps), _ptr(d_out), _ptr(e_out),
+                                              _ptr(Q), _ptr(rot), _stream(stream))
+    if st != 0:
+        raise BedError(st, "bed_tridiag_qr_sweeps")
+    return d_out, e_out, Q, rot
 
 
 BED_FN_SQRT = 0

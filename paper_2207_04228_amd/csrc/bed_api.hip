@@ -102,6 +102,35 @@ int bed_tridiag_qr(const float* d, const float* e, int batch, int n, float* eval
     return run(args, bed::kQrOnly, evecs != nullptr, stream);
 }
 
+int bed_tridiag_qr_sweeps(const float* d, const float* e, int batch, int n, int sweeps, float* d_out,
+                          float* e_out, float* Q, unsigned* rotations, void* stream) {
+    int st = check_common(batch, n);
+    if (st != BED_OK) return st;
+    if (n > 64) return BED_ERR_N;
+    if (sweeps < 1) return BED_ERR_ARG;
+    if (batch == 0) return BED_OK;
+    if (!d || !e || !d_out || !e_out || !Q) return BED_ERR_NULL;
+    if (misaligned(d) || misaligned(e) || misaligned(d_out) || misaligned(e_out) || misaligned(Q) ||
+        misaligned(rotations))
+        return BED_ERR_ALIGN;
+    const size_t mat = (size_t)batch * n * n * sizeof(float), vec = (size_t)batch * n * sizeof(float);
+    if (overlaps(d, vec, d_out, vec) || overlaps(d, vec, e_out, vec) || overlaps(e, vec, d_out, vec) ||
+        overlaps(e, vec, e_out, vec) || overlaps(d, vec, Q, mat) || overlaps(e, vec, Q, mat) ||
+        overlaps(d_out, vec, e_out, vec) || overlaps(d_out, vec, Q, mat) || overlaps(e_out, vec, Q, mat))
+        return BED_ERR_ALIAS;
+    bed::KernelArgs args{};
+    args.d_in = d;
+    args.e_in = e;
+    args.d_out = d_out;
+    args.e_out = e_out;
+    args.evecs = Q;
+    args.rotations = rotations;
+    args.sweep_cap = (uint32_t)sweeps;
+    args.batch = batch;
+    args.n = n;
+    return run(args, bed::kQrPartial, true, stream);
+}
+
 int bed_spd_fn(const float* A, int batch, int n, int fn, float floor, float* out, float* evals, int* info,
                void* stream) {
     int st = check_common(batch, n);

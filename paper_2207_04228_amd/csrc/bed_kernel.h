@@ -7,7 +7,7 @@
 
 namespace bed {
 
-enum Stage { kFull = 0, kTridiagOnly = 1, kQrOnly = 2, kSpectral = 3 };
+enum Stage { kFull = 0, kTridiagOnly = 1, kQrOnly = 2, kSpectral = 3, kQrPartial = 4 };
 enum SpectralFn { kFnSqrt = 0, kFnInvSqrt = 1 };
 
 struct KernelArgs {
@@ -21,6 +21,7 @@ struct KernelArgs {
     float* fn_out;       // [batch][n][n]            (kSpectral) V f(lambda) V^T
     float fn_floor;      // eigenvalues are raised to this floor before f is applied (kSpectral)
     int fn;              // SpectralFn (kSpectral)
+    uint32_t sweep_cap;  // at most this many sweeps (0: the default cap of 30 n); kQrPartial stops there
     int* info;           // [batch] or nullptr
     uint32_t* rotations; // [batch] or nullptr
     int batch;

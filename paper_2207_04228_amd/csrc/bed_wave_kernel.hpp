@@ -213,7 +213,7 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
                                               const int n, uint32_t& rotations, int& info,
                                               float (&d_lane)[(N + 63) / 64], const KernelArgs& args, const int b) {
     const bool roleB = lane >= 32;
-    const uint32_t cap = 30u * (uint32_t)n;
+    const uint32_t cap = args.sweep_cap ? args.sweep_cap : 30u * (uint32_t)n;
     uint32_t sweeps = 0;
     // Off-diagonal k = lane + 64 * bank is watched by this lane: e[k] not yet deflated.
     constexpr int NB = (N + 63) / 64;
@@ -509,14 +509,14 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
         info += max((int)__builtin_popcountll(nz[bk]), (int)__builtin_popcountll(bad));
         d_lane[bk] = dl[bk];
     }
-    (void)args;
     (void)b;
 }
 
 // ---------------------------------------------------------------------------
 // N      register-array size (4, 8, 12, 16, 20, 24, 28, 32, 40, 48, 56, 64); n <= N at run time
 // WANT_V accumulate eigenvectors
-// STAGE  kFull, kTridiagOnly (stage hook 1), kQrOnly (stage hook 2)
+// STAGE  kFull, kTridiagOnly (stage hook 1), kQrOnly (stage hook 2), kQrPartial (stage hook 3:
+//        a given number of sweeps on a given tridiagonal, result left unsorted)
 // Shifts: both eigenvalues of the trailing 2x2 block of the active window are taken
 // once per outer iteration and used by two sweeps over the same window (Sec. 3.2.2).
 // ---------------------------------------------------------------------------
@@ -549,7 +549,8 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
 
     float inv_scale = 1.f;
 
-    if (STAGE != kQrOnly && HALF && WANT_V) {
+    constexpr bool GIVEN_T = (STAGE == kQrOnly || STAGE == kQrPartial);
+    if (!GIVEN_T && HALF && WANT_V) {
         // ---- rows fit in half a wavefront and P is wanted: the lower half holds the rows of
         // the working matrix, the upper half the rows of the accumulated reflector product
         // P (Eq. (8)).  One instruction stream serves both: the dot product with u gives
@@ -628,7 +629,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
 #pragma unroll
         for (int c = 0; c < N; ++c) sV[c * LD + row] = from_upper_half(x[c]);
         wave_sync();
-    } else if (STAGE != kQrOnly) {
+    } else if (!GIVEN_T) {
         float a[N];
         float v[N];
 #pragma unroll
@@ -784,6 +785,24 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         qr_iterations<N, HALF, WANT_V, LD>(sP, sV, lane, row, n, rotations, info, d_lane, args, b);
         const float dl = d_lane[0];
         const int vrow = row;
+        if (STAGE == kQrPartial) {
+            // stage hook 3: the tridiagonal and the accumulated rotations as they stand
+            if (lane < n) {
+                args.d_out[(size_t)b * n + lane] = sP[lane].y * inv_scale;
+                args.e_out[(size_t)b * n + lane] = (lane < n - 1) ? sP[lane + 1].x * inv_scale : 0.f;
+            }
+            if (WANT_V) {
+                float* __restrict__ Vb = args.evecs + (size_t)b * n * n;
+                const float rcp_n = 1.0f / (float)n;
+                for (int idx = lane; idx < n * n; idx += 64) {
+                    int i = (int)(((float)idx + 0.5f) * rcp_n);
+                    int j = idx - i * n;
+                    Vb[idx] = sV[j * LD + i];
+                }
+            }
+            if (lane == 0 && args.rotations) args.rotations[b] = rotations;
+            return;
+        }
 
         if (STAGE == kSpectral) {
             // ---- F = V f(Lambda) V^T (Sec. 4.2-4.4, App. B: A^{-1/2} for whitening, A^{1/2} for
@@ -871,6 +890,7 @@ static hipError_t launch_n(const KernelArgs& args, int stage, bool want_v, hipSt
                       : launch_one<N, false, kQrOnly>(args, stream);
     }
     if (stage == kSpectral) return launch_one<N, true, kSpectral>(args, stream);
+    if (stage == kQrPartial) return launch_one<N, true, kQrPartial>(args, stream);
     return want_v ? launch_one<N, true, kFull>(args, stream)
                   : launch_one<N, false, kFull>(args, stream);
 }

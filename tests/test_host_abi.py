@@ -28,7 +28,7 @@ def _declared_symbols():
 
 def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
-    assert {"bed_syevd", "bed_syevd_info", "bed_tridiag", "bed_tridiag_qr", "bed_spd_fn", "bed_syevd_backward", "bed_spd_fn_backward",
+    assert {"bed_syevd", "bed_syevd_info", "bed_tridiag", "bed_tridiag_qr", "bed_tridiag_qr_sweeps", "bed_spd_fn", "bed_syevd_backward", "bed_spd_fn_backward",
             "bed_status_string", "bed_version"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
@@ -70,6 +70,12 @@ def test_argument_validation_is_host_side(lib):
     assert lib.bed_spd_fn(A, 1, 4, 0, f(0.0), p(0x10020), None, None, None) == -6  # out overlaps A
     assert lib.bed_spd_fn(A, 0, 4, 0, f(0.0), V, None, None, None) == 0
     O = p(0x50000)
+    D2, E2 = p(0x60000), p(0x70000)
+    assert lib.bed_tridiag_qr_sweeps(A, L, 1, 4, 0, D2, E2, V, None, None) == -7      # sweeps < 1
+    assert lib.bed_tridiag_qr_sweeps(A, L, 1, 65, 2, D2, E2, V, None, None) == -3     # hook limited to n <= 64
+    assert lib.bed_tridiag_qr_sweeps(A, L, 1, 4, 2, D2, E2, None, None, None) == -1
+    assert lib.bed_tridiag_qr_sweeps(A, L, 1, 4, 2, A, E2, V, None, None) == -6
+    assert lib.bed_tridiag_qr_sweeps(A, L, 0, 4, 2, D2, E2, V, None, None) == 0
     assert lib.bed_syevd_backward(L, V, None, None, 1, 4, 0, 9, f(0.0), O, None) == -1      # no gradient given
     assert lib.bed_syevd_backward(None, V, L, None, 1, 4, 0, 9, f(0.0), O, None) == -1
     assert lib.bed_syevd_backward(L, V, L, None, 1, 4, 2, 9, f(0.0), O, None) == -7         # unknown mode
