@@ -27,7 +27,9 @@ namespace bed {
 
 namespace lanek {
 
-constexpr float kEps = 1.1920929e-7f;   // 2^-23: relative deflation tolerance
+// 4 * 2^-23: relative deflation tolerance (well above the rounding level that the recurrence
+// leaves on the off-diagonals inside a cluster of equal eigenvalues)
+constexpr float kEps = 4.7683716e-7f;
 constexpr float kTinyE = 1.0e-18f;      // absolute floor for |e| (matrix pre-scaled to max|a| in [0.5,1))
 constexpr float kTinyG = 1.0e-18f;      // floor for the rotation pivot
 constexpr float kTinyAlpha = 1.0e-35f;  // |x|^2 below this: column already reduced
@@ -226,13 +228,18 @@ __global__ __launch_bounds__(64) void lane_kernel(KernelArgs args) {
         sweeps += (hi > lo) ? 1u : 0u;
     };
 
+    uint32_t live_prev = ~0u, stall = 0;      // iterations of this lane since its last deflation
     while (true) {
-        // deflation test over every live off-diagonal of this lane
+        // deflation test over every live off-diagonal of this lane; a window that has not
+        // deflated anything for 12 (24) iterations gets a tolerance 8 (64) times wider
+        const float tol = kEps * (stall >= 24u ? 64.f : (stall >= 12u ? 8.f : 1.f));
 #pragma unroll
         for (int k = 0; k < N - 1; ++k) {
-            const bool negl = fabsf(e[k]) <= fmaxf(kEps * (fabsf(d[k]) + fabsf(d[k + 1])), kTinyE);
+            const bool negl = fabsf(e[k]) <= fmaxf(tol * (fabsf(d[k]) + fabsf(d[k + 1])), kTinyE);
             live = negl ? (live & ~(1u << k)) : live;
         }
+        stall = (live == live_prev) ? stall + 1u : 0u;
+        live_prev = live;
         const bool active = (live != 0) && (sweeps < cap);
         if (__ballot(active) == 0) break;
         // this lane's window: the lowest run of live entries (empty for a finished lane)

@@ -35,7 +35,13 @@ namespace bed {
 
 namespace {
 
-constexpr float kEps = 1.1920929e-7f;   // 2^-23: relative deflation tolerance
+// Relative deflation tolerance: |e_k| <= kEps (|d_k| + |d_k+1|), kEps = 4 * 2^-23.  Inside a
+// cluster of (nearly) equal eigenvalues the recurrence leaves off-diagonals at the rounding
+// level of the diagonal, one to two units in the last place of d; a tolerance of 2^-23 is only
+// two such units when d is just above a power of two, and windows of repeated eigenvalues then
+// hover around it without ever deflating.
+constexpr float kEps = 4.7683716e-7f;
+constexpr uint32_t kStallIterations = 12;   // iterations without any deflation before the tolerance is widened
 constexpr float kTinyE = 1.0e-18f;      // absolute floor for |e| (matrix is pre-scaled to max|a| in [0.5,1))
 constexpr float kTinyG = 1.0e-18f;      // floor for |g| in a rotation (keeps f^2+g^2 a normal number)
 constexpr float kTinyAlpha = 1.0e-35f;  // |x|^2 below this: column already reduced, reflector skipped
@@ -224,13 +230,21 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
         live[bk] = lane + 64 * bk < n - 1;
         dl[bk] = 0.f;
     }
-    uint64_t nz[NB];
+    uint64_t nz[NB], nz_prev[NB];
+#pragma unroll
+    for (int bk = 0; bk < NB; ++bk) nz_prev[bk] = ~0ull;
+    uint32_t stall = 0;                 // iterations since the last deflation
     BED_PROBE_INIT();
     while (true) {
         BED_PROBE(0);
+        // A window that has not deflated anything for kStallIterations iterations gets a wider
+        // tolerance (x8, then x64): every matrix finishes, at worst with that eigenvalue less
+        // accurate, instead of one stuck window using up the sweep cap for the whole matrix.
+        const float tol = kEps * (stall >= 2 * kStallIterations ? 64.f : (stall >= kStallIterations ? 8.f : 1.f));
         // deflation test, lane-parallel: the lane looks at e[k], d[k], d[k+1]
         float el[NB], dnext[NB];
         uint64_t any = 0;
+        bool same = true;
 #pragma unroll
         for (int bk = 0; bk < NB; ++bk) {
             const int k = lane + 64 * bk;
@@ -243,10 +257,13 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
                 el[bk] = pk1.x;
                 dnext[bk] = pk1.y;
             }
-            live[bk] = live[bk] && !(fabsf(el[bk]) <= fmaxf(kEps * (fabsf(dl[bk]) + fabsf(dnext[bk])), kTinyE));
+            live[bk] = live[bk] && !(fabsf(el[bk]) <= fmaxf(tol * (fabsf(dl[bk]) + fabsf(dnext[bk])), kTinyE));
             nz[bk] = __ballot(live[bk]);
             any |= nz[bk];
+            same = same && nz[bk] == nz_prev[bk];
+            nz_prev[bk] = nz[bk];
         }
+        stall = same ? stall + 1 : 0;
         if (any == 0 || sweeps >= cap) break;
         // active window [lo, hi]: e[hi-1] is the last live entry, e[lo-1] the last dead one below it
         int hi, lo;
