@@ -109,11 +109,13 @@ def main(argv=None) -> int:
 
     # rotation counts (for the flop model), outside the timed region
     rot_mean = {}
+    rot_max = {}
     for n, A, ev, V in bufs:
         _, _, info, rot = binding.bed_syevd_info(A, ev, V)
         torch.cuda.synchronize()
         assert int(info.max().item()) == 0, "non-converged matrix in the benchmark input"
         rot_mean[n] = float(rot.float().mean().item())
+        rot_max[n] = int(rot.max().item())      # a batch-uniform window would run every matrix this long
 
     def step():
         for n, A, ev, V in bufs:
@@ -168,6 +170,7 @@ def main(argv=None) -> int:
             "kernel_us_median": float(np.median(durs)) * 1e6,
             "matrices_per_s": B / mean,
             "rotations_mean": rot_mean[n],
+            "rotations_max": rot_max[n],
             "flops_per_launch": fl,
             "tflops": fl / mean / 1e12,
             "frac_fp32_valu": fl / mean / 1e12 / PEAK_FP32_TFLOPS,

@@ -216,7 +216,7 @@ const char* bed_status_string(int status) {
         case BED_OK: return "BED_OK";
         case BED_ERR_NULL: return "BED_ERR_NULL: a required pointer is NULL";
         case BED_ERR_BATCH: return "BED_ERR_BATCH: batch must be >= 0";
-        case BED_ERR_N: return "BED_ERR_N: n must be in 1..64";
+        case BED_ERR_N: return "BED_ERR_N: n must be in 1..128 (1..64 for bed_tridiag_qr_sweeps)";
         case BED_ERR_ALIGN: return "BED_ERR_ALIGN: pointers must be 4-byte aligned";
         case BED_ERR_LAUNCH: return "BED_ERR_LAUNCH: kernel launch failed";
         case BED_ERR_ALIAS: return "BED_ERR_ALIAS: buffers overlap";
