@@ -262,7 +262,9 @@ __global__ __launch_bounds__(64) void lane_kernel(KernelArgs args) {
         const float den = delta + ((delta >= 0.f) ? rt : -rt);
         const float tt = (tb * tb) * __builtin_amdgcn_rcpf(guard_g(den));
         const float mu1 = td - tt;
-        const float mu2 = ta + tt;
+        // after 5 iterations without a deflation both sweeps use mu1: the pair (mu1, mu2) has
+        // fixed points (diagonal 1, 0, 1 with off-diagonals 1 is one)
+        const float mu2 = (stall >= 5u) ? mu1 : ta + tt;
         sweep(lo, hi, mu1);
         // a window that was the 2x2 block itself is diagonalised by the exact-shift step:
         // its off-diagonal is set to zero and the second sweep is skipped

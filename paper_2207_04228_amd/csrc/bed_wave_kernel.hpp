@@ -41,6 +41,11 @@ namespace {
 // two such units when d is just above a power of two, and windows of repeated eigenvalues then
 // hover around it without ever deflating.
 constexpr float kEps = 4.7683716e-7f;
+// The pair of sweeps with both eigenvalues of the trailing block has fixed points (the 3x3
+// matrix with diagonal 1, 0, 1 and off-diagonals 1 is mapped onto itself up to signs), as the
+// double-shift QR step has in general.  After this many iterations without any deflation both
+// sweeps use the eigenvalue closer to the last diagonal entry, which leaves such a point.
+constexpr uint32_t kExceptionalAfter = 5;
 constexpr uint32_t kStallIterations = 12;   // iterations without any deflation before the tolerance is widened
 constexpr float kTinyE = 1.0e-18f;      // absolute floor for |e| (matrix is pre-scaled to max|a| in [0.5,1))
 constexpr float kTinyG = 1.0e-18f;      // floor for |g| in a rotation (keeps f^2+g^2 a normal number)
@@ -292,7 +297,7 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
         const float den = delta + ((delta >= 0.f) ? rt : -rt);
         const float tt = (tb * tb) * __builtin_amdgcn_rcpf(den);
         const float mu1 = td - tt;          // eigenvalue closer to the last diagonal entry
-        const float mu2 = ta + tt;          // the other eigenvalue of the block
+        const float mu2 = (stall >= kExceptionalAfter) ? mu1 : ta + tt;   // the other eigenvalue of the block
 
         // Inputs of rotation t: (e[t], d[t+1]) = sP[t+1] and column t+1 of V.  They are
         // fetched two rotations ahead into two slots used in alternation (slot 0: rotations

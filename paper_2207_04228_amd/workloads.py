@@ -126,3 +126,67 @@ def config5(n: int, batch: int = 256, return_parts: bool = False):
 def headline_points():
     """The four (n, A) points of the headline metric: batch 512, n = 4/8/16/32."""
     return [(4, config2(512)), (8, config3(8)), (16, config3(16)), (32, config3(32))]
+
+
+def wilkinson_tridiagonal(n: int) -> np.ndarray:
+    """W_n^+: diagonal |i - (n-1)/2|, off-diagonals 1 (its large eigenvalues come in pairs
+    that agree to many digits)."""
+    return (np.diag(np.abs(np.arange(n) - (n - 1) / 2.0)) + np.diag(np.ones(n - 1), 1)
+            + np.diag(np.ones(n - 1), -1))
+
+
+def glued_wilkinson(n: int, blocks: int = 4, glue: float = 1e-6) -> np.ndarray:
+    """Wilkinson blocks coupled by a tiny off-diagonal entry: clusters of eigenvalues whose
+    vectors are spread over several blocks."""
+    G = np.zeros((n, n))
+    k = max(2, n // blocks)
+    for j in range(0, n, k):
+        kk = min(k, n - j)
+        G[j:j + kk, j:j + kk] = wilkinson_tridiagonal(kk)
+        if j > 0:
+            G[j, j - 1] = G[j - 1, j] = glue
+    return G
+
+
+def structured_cases(n: int, batch: int, seed: int):
+    """[(name, A float32 [b][n][n])]: matrices with structure that stresses deflation,
+    scaling and clustering rather than the covariance-like bulk of the configs: graded and
+    +- paired spectra, extreme scales, Wilkinson and glued Wilkinson matrices (plain and
+    hidden by a random orthogonal similarity), rank one, identity, zero, sparse, arrow,
+    near-identity, rank two, Hilbert and Kac-Murdock-Szego matrices."""
+    rng = np.random.default_rng(seed)
+    idx = np.arange(n)
+    out = []
+
+    def add(name, A):
+        out.append((name, np.ascontiguousarray(A, dtype=np.float32)))
+
+    lam = np.logspace(-10, 0, n)[None, :].repeat(batch, 0) * rng.uniform(0.5, 1, (batch, n))
+    add("graded", from_spectrum(lam, seed=seed + 1))
+    lam = np.concatenate([-np.arange(1, n // 2 + 1), np.arange(1, n - n // 2 + 1)])[None, :].repeat(batch, 0)
+    add("plus-minus pairs", from_spectrum(lam.astype(np.float64), seed=seed + 2))
+    A = from_spectrum(rng.uniform(0.1, 1, (batch, n)), seed=seed + 3)
+    add("scale 1e-30", A * np.float32(1e-30))
+    add("scale 1e+30", A * np.float32(1e30))
+    add("wilkinson", wilkinson_tridiagonal(n)[None].repeat(2, 0))
+    if n >= 8:
+        G = glued_wilkinson(n)
+        add("glued wilkinson", G[None].repeat(2, 0))
+        Q = haar_orthogonal(2, n, rng)
+        add("glued wilkinson, rotated", Q @ G @ np.swapaxes(Q, 1, 2))
+    add("all ones", np.ones((2, n, n)))
+    add("identity", np.eye(n)[None].repeat(2, 0))
+    add("zero", np.zeros((2, n, n)))
+    S = rng.standard_normal((batch, n, n)) * (rng.uniform(0, 1, (batch, n, n)) < 0.1)
+    add("sparse", (S + np.swapaxes(S, 1, 2)) / 2)
+    Ar = np.zeros((batch, n, n))
+    Ar[:, idx, idx] = rng.uniform(0, 1, (batch, n))
+    Ar[:, 0, :] = Ar[:, :, 0] = rng.standard_normal((batch, n))
+    add("arrow", Ar)
+    P = rng.standard_normal((batch, n, n)) * 1e-7
+    add("near identity", np.eye(n)[None] * 3 + (P + np.swapaxes(P, 1, 2)) / 2)
+    X = rng.standard_normal((batch, n, 2))
+    add("rank two", X @ np.swapaxes(X, 1, 2))
+    add("hilbert", (1.0 / (idx[:, None] + idx[None, :] + 1.0))[None].repeat(2, 0))
+    add("kac-murdock-szego", np.exp(-3.0 * np.abs(idx[:, None] - idx[None, :]))[None].repeat(2, 0))
+    return out
