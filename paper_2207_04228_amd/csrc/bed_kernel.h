@@ -26,9 +26,6 @@ struct KernelArgs {
     uint32_t* rotations; // [batch] or nullptr
     int batch;
     int n;
-#ifdef BED_PROFILE
-    long long* prof;     // [batch][8] development-only phase timers
-#endif
 };
 
 // Gradient kernels (bed_grad.hip).

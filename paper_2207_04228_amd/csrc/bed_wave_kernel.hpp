@@ -20,17 +20,6 @@
 
 #include "bed_kernel.h"
 
-#ifdef BED_PROFILE
-// Development-only phase timers (cycle counter deltas accumulated per probe id).
-#define BED_PROBE_INIT() long long prof_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}; long long prof_last = clock64(); int prof_id = 7
-#define BED_PROBE(i) do { long long now_ = clock64(); prof_acc[prof_id] += now_ - prof_last; prof_last = now_; prof_id = (i); } while (0)
-#define BED_PROBE_DUMP() do { BED_PROBE(7); if (lane == 0 && args.prof) for (int q_ = 0; q_ < 8; ++q_) args.prof[(size_t)b * 8 + q_] = prof_acc[q_]; } while (0)
-#else
-#define BED_PROBE_INIT() do {} while (0)
-#define BED_PROBE(i) do {} while (0)
-#define BED_PROBE_DUMP() do {} while (0)
-#endif
-
 namespace bed {
 
 namespace {
@@ -239,9 +228,7 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
 #pragma unroll
     for (int bk = 0; bk < NB; ++bk) nz_prev[bk] = ~0ull;
     uint32_t stall = 0;                 // iterations since the last deflation
-    BED_PROBE_INIT();
     while (true) {
-        BED_PROBE(0);
         // A window that has not deflated anything for kStallIterations iterations gets a wider
         // tolerance (x8, then x64): every matrix finishes, at worst with that eigenvalue less
         // accurate, instead of one stuck window using up the sweep cap for the whole matrix.
@@ -287,7 +274,6 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
             return (NB == 1 || idx < 64) ? read_lane(v[0], idx & 63) : read_lane(v[NB - 1], idx - 64);
         };
 
-        BED_PROBE(1);
         // eigenvalues of the trailing block [[ta, tb], [tb, td]] (App. A.3), smaller-angle root first
         const float ta = at(dl, hi - 1);
         const float tb = at(el, hi - 1);
@@ -326,7 +312,6 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
             // from registers.  At step t: B handles row t-2 with A's outputs of step t-1,
             // while A handles row t.
             float pE, pD, pV = 0.f;     // A's outputs of the previous step
-            BED_PROBE(2);
             // t = lo: A rotates row lo
             chain_rotate<WANT_V>(A, q0.x, q0.y, y0, pE, pD, pV);
             BED_REFILL(q0, y0, lo);
@@ -343,7 +328,6 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
                 if (WANT_V) sV[hi * LD + vrow] = pV;
                 rotations += 1u;
                 sweeps += 1;
-                BED_PROBE(5);
             } else if (HALF) {
                 // Role lanes: lanes 0..31 carry sweep A, lanes 32..63 carry sweep B, so one
                 // instruction stream advances both sweeps by one rotation per step.
@@ -353,7 +337,6 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
                 // t = lo + 1: A rotates row lo+1 (still computed by every lane)
                 chain_rotate<WANT_V>(A, q1.x, q1.y, y1, pE, pD, pV);
                 BED_REFILL(q1, y1, lo + 1);
-                BED_PROBE(3);
                 Chain S;                                   // this lane's chain: A or B
                 S.g = roleB ? (sD - mu2) : A.g;
                 S.s = roleB ? 1.f : A.s;
@@ -402,7 +385,6 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
                     xP += 1;
                 }
 #undef BED_STEPH
-                BED_PROBE(4);
                 // The three closing steps belong to B alone; the A lanes' stores would now land
                 // beyond the window, so they are parked in the padding behind the arrays.
                 xV = roleB ? xV : (sV + (N + 3) * LD + vrow);
@@ -425,7 +407,6 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
                 if (WANT_V) const_cast<float*>(xV)[2 * LD] = fV;
                 rotations += 2u * (uint32_t)(hi - lo);
                 sweeps += 2;
-                BED_PROBE(5);
             } else {
                 // Rows need the whole wavefront.  The scalar recurrences of the two sweeps
                 // still run in the two halves (lanes 0..31 sweep A, lanes 32..63 sweep B, two
@@ -437,7 +418,6 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
                 // t = lo + 1: A rotates row lo+1 (still computed by every lane)
                 chain_rotate<WANT_V>(A, q1.x, q1.y, y1, pE, pD, pV);
                 BED_REFILL(q1, y1, lo + 1);
-                BED_PROBE(3);
                 Chain S;                                   // this lane's recurrence: A or B (no V part)
                 S.g = roleB ? (sD - mu2) : A.g;
                 S.s = roleB ? 1.f : A.s;
@@ -488,7 +468,6 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
                     xP += 1;
                 }
 #undef BED_STEPW
-                BED_PROBE(4);
                 // closing steps: B alone; the A lanes' T stores are parked in the padding
                 xP = roleB ? xP : (sP + (N + 3));
                 float fE, fD, fx;
@@ -516,13 +495,11 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
                 if (WANT_V) xVp[2 * LD] = xB;
                 rotations += 2u * (uint32_t)(hi - lo);
                 sweeps += 2;
-                BED_PROBE(5);
             }
         }
 #undef BED_REFILL
         wave_sync();
     }
-    BED_PROBE_DUMP();
     info = 0;
 #pragma unroll
     for (int bk = 0; bk < NB; ++bk) {
