@@ -264,6 +264,18 @@ def main(argv=None) -> int:
             evp = torch.empty((batch, n), dtype=torch.float32, device=dev)
             Vp = torch.empty((batch, n, n), dtype=torch.float32, device=dev)
             extras["paper_shapes_us"][f"{batch}x{n}x{n}"] = timed(lambda: binding.bed_syevd(Ap, evp, Vp), 20) * 1e6
+    if not a.no_extras:
+        # the paper's fixed-budget procedure (n iterations, eps 1e-5) on the same inputs: one
+        # launch per iteration; what is left of the sub-diagonal says how far from converged it ends
+        extras["lockstep"] = {}
+        for n, A, ev, V in bufs:
+            ws = torch.empty((1 << 20,), dtype=torch.int32, device=dev)
+            for name, uniform in (("uniform", True), ("per_matrix", False)):
+                t = timed(lambda: binding.bed_syevd_lockstep(A, 1e-5, n, uniform, workspace=ws), 5)
+                _, _, off, red = binding.bed_syevd_lockstep(A, 1e-5, n, uniform, workspace=ws)
+                extras["lockstep"][f"n{n}_{name}"] = {
+                    "us": t * 1e6, "rows_dropped_mean": float(red.float().mean().item()),
+                    "offdiag_left_max": float(off.max().item())}
     for n, batch in (() if a.no_extras else ((4, 65536), (8, 65536), (16, 4096), (32, 4096), (64, 256), (128, 256))):
         A32b = (workloads.config2(batch) if n == 4 else
                 workloads.config3(n, batch=batch) if n <= 32 else

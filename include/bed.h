@@ -19,12 +19,14 @@
 #ifndef BED_H
 #define BED_H
 
+#include <stddef.h>
+
 #ifdef __cplusplus
 extern "C" {
 #endif
 
 #define BED_MAX_N 128
-#define BED_VERSION 300 /* major*10000 + minor*100 + patch: 0.3.0 (spectral function, gradients, n <= 128) */
+#define BED_VERSION 400 /* major*10000 + minor*100 + patch: 0.4.0 (0.3.0 + the fixed-budget lock-step procedure) */
 
 typedef enum {
     BED_OK = 0,
@@ -187,6 +189,37 @@ int bed_syevd_backward(const float* evals, const float* evecs, const float* grad
  */
 int bed_spd_fn_backward(const float* evals, const float* evecs, const float* grad_out, int batch,
                         int n, int fn, float floor, float* grad_A, void* stream);
+
+/*
+ * The paper's fixed-budget procedure as written (Sec. 3.2.3, App. B), kept for comparison with
+ * bed_syevd; it is NOT a solver to rely on (the budget can end far from convergence).  After the
+ * tridiagonalisation of Sec. 3.1, `iterations` outer iterations (App. B: n), each two shifted QR
+ * steps over the leading m x m window with the two eigenvalues of its trailing 2x2 block, both
+ * taken from the matrix the iteration starts from (Sec. 3.2.2, App. A.3; the one closer to the
+ * last diagonal entry first).  After an iteration the window shrinks by one row if the last
+ * sub-diagonal entry of the window is at most `epsilon` in magnitude (App. B: 1e-5; absolute, that
+ * entry only): with uniform = 1 for the whole batch at once, when every matrix passes, as a
+ * batched tensor forces; with uniform = 0 for each matrix on its own.  No other deflation, no
+ * convergence test, no pre-scaling of A (the test is absolute).  One launch per iteration.
+ *
+ *   A            device, const, [batch][n][n], lower triangle read, n in 1 .. 64 (BED_ERR_N beyond)
+ *   epsilon      >= 0, finite;  iterations >= 0;  uniform 0 or 1   (else BED_ERR_ARG)
+ *   evals        device, [batch][n]: diag(T) when the budget ends, ascending
+ *   evecs        device, [batch][n][n] or NULL: P Q_1 Q_2 ..., columns in the order of evals
+ *                (working storage between the launches)
+ *   offdiag      device, [batch][n] or NULL: |sub-diagonal| of T when the budget ends, in the
+ *                order of T before the sort (offdiag[b][k] couples rows k, k+1; last entry 0);
+ *                ||A V - V diag(evals)||_F = sqrt(2 sum offdiag^2) up to rounding
+ *   reductions   device, [batch] or NULL: rows dropped (equal for all matrices when uniform)
+ *   workspace    device, at least bed_syevd_lockstep_workspace(batch, n, iterations) bytes, 4-byte
+ *                aligned, owned by the caller, contents undefined afterwards; workspace_bytes is
+ *                its size (BED_ERR_ARG if too small).  Calls that share a workspace must not overlap.
+ * No buffer may alias another.  Asynchronous on `stream` like every other entry point.
+ */
+size_t bed_syevd_lockstep_workspace(int batch, int n, int iterations);
+int bed_syevd_lockstep(const float* A, int batch, int n, float epsilon, int iterations, int uniform,
+                       float* evals, float* evecs, float* offdiag, int* reductions,
+                       void* workspace, size_t workspace_bytes, void* stream);
 
 /* Human-readable name of a bed_status value (static storage). */
 const char* bed_status_string(int status);

@@ -58,15 +58,19 @@ def wilkinson_pair(a: float, b: float, d: float):
     return lo, hi
 
 
-def qr_step(T: np.ndarray, m: int, mu: float):
+def qr_step(T: np.ndarray, m: int, mu: float, pivots: list | None = None):
     """Sec. 3.2.1 with the shift of Sec. 3.2.2 on the leading m x m block:
     T - mu I = Q R by m-1 Givens rotations (rotation k annihilates entry (k+1, k)),
-    then T' = R Q + mu I.  Returns the updated full matrix and Q (m x m)."""
+    then T' = R Q + mu I.  Returns the updated full matrix and Q (m x m).  If `pivots` is a
+    list, the length r of the vector each rotation is computed from is appended to it (a
+    rotation from a tiny vector is determined by rounding errors; bookkeeping for tests)."""
     M = T[:m, :m] - mu * np.eye(m)
     Q = np.eye(m)
     for k in range(m - 1):
         x1, x2 = M[k, k], M[k + 1, k]
         r = np.hypot(x1, x2)
+        if pivots is not None:
+            pivots.append(r)
         c, s = (1.0, 0.0) if r == 0.0 else (x1 / r, x2 / r)
         Gt = np.eye(m)                          # G^T [x1; x2] = [r; 0]
         Gt[k, k], Gt[k, k + 1], Gt[k + 1, k], Gt[k + 1, k + 1] = c, s, -s, c
@@ -89,6 +93,7 @@ class LockstepResult:
     offdiag: np.ndarray               # [batch][n-1] sub-diagonal left at the end (dropped entries as they were when dropped)
     window: list = field(default_factory=list)     # window size at the start of each iteration: [iterations][batch]
     last_e: list = field(default_factory=list)     # |last sub-diagonal of the window| after each iteration: [iterations][batch]
+    min_pivot: np.ndarray = None      # [batch] shortest vector any rotation of the run was computed from
 
 
 def tridiag_qr_lockstep(d: np.ndarray, e: np.ndarray, eps: float = 1e-5, iterations: int | None = None,
@@ -112,6 +117,7 @@ def tridiag_qr_lockstep(d: np.ndarray, e: np.ndarray, eps: float = 1e-5, iterati
     V = [np.eye(n) if V0 is None else np.array(V0[b], dtype=np.float64) for b in range(batch)]
     m = np.full(batch, n, dtype=np.int64)
     res = LockstepResult(None, None, None, None)
+    pivots = [[] for _ in range(batch)]
     for _ in range(iterations):
         res.window.append(m.copy())
         shifts = [wilkinson_pair(T[b][m[b] - 2, m[b] - 2], T[b][m[b] - 1, m[b] - 2], T[b][m[b] - 1, m[b] - 1])
@@ -122,7 +128,7 @@ def tridiag_qr_lockstep(d: np.ndarray, e: np.ndarray, eps: float = 1e-5, iterati
                 mb = int(m[b])
                 if mb < 2:
                     continue
-                T[b], Q = qr_step(T[b], mb, shifts[b][half])
+                T[b], Q = qr_step(T[b], mb, shifts[b][half], pivots[b])
                 V[b][:, :mb] = V[b][:, :mb] @ Q
                 last[b] = abs(T[b][mb - 1, mb - 2])
             if half == 1:
@@ -142,6 +148,7 @@ def tridiag_qr_lockstep(d: np.ndarray, e: np.ndarray, eps: float = 1e-5, iterati
         Vs = np.take_along_axis(Vs, order[:, None, :], axis=2)
     res.evals, res.evecs = lam, Vs
     res.reductions = n - m
+    res.min_pivot = np.array([min(pv) if pv else np.inf for pv in pivots])
     res.offdiag = np.stack([np.diag(T[b], -1) for b in range(batch)]) if n > 1 else np.zeros((batch, 0))
     return res
 

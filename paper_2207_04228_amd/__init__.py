@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     bed_syevd_backward,
     bed_syevd,
     bed_syevd_info,
+    bed_syevd_lockstep,
     bed_tridiag,
     bed_tridiag_qr,
     bed_tridiag_qr_sweeps,

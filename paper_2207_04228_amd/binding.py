@@ -53,6 +53,10 @@ def load_library():
         lib.bed_syevd_backward.restype = ci
         lib.bed_spd_fn_backward.argtypes = [vp, vp, vp, ci, ci, ci, ctypes.c_float, vp, vp]
         lib.bed_spd_fn_backward.restype = ci
+        lib.bed_syevd_lockstep_workspace.argtypes = [ci, ci, ci]
+        lib.bed_syevd_lockstep_workspace.restype = ctypes.c_size_t
+        lib.bed_syevd_lockstep.argtypes = [vp, ci, ci, ctypes.c_float, ci, ci, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.bed_syevd_lockstep.restype = ci
         lib.bed_status_string.argtypes = [ci]
         lib.bed_status_string.restype = ctypes.c_char_p
         lib.bed_version.argtypes = []
@@ -184,6 +188,33 @@ def bed_tridiag_qr_sweeps(d, e, sweeps, *, stream=None):
     if st != 0:
         raise BedError(st, "bed_tridiag_qr_sweeps")
     return d_out, e_out, Q, rot
+
+
+def bed_syevd_lockstep(A, epsilon=1e-5, iterations=None, uniform=True, *, want_vectors=True, workspace=None,
+                       stream=None):
+    """The paper's fixed-budget procedure (n outer iterations by default, absolute threshold on the
+    last sub-diagonal entry, window shared by the batch if `uniform`).
+    Returns (evals, evecs or None, offdiag [batch, n], reductions int32 [batch])."""
+    import torch
+    _check_dev(A, "A", torch.float32)
+    batch, n, n2 = A.shape
+    if n != n2:
+        raise ValueError("A must be [batch, n, n]")
+    iterations = n if iterations is None else int(iterations)
+    lib = load_library()
+    need = int(lib.bed_syevd_lockstep_workspace(batch, n, iterations))
+    if workspace is None:
+        workspace = torch.empty((max(need, 4) // 4,), dtype=torch.int32, device=A.device)
+    evals = torch.empty((batch, n), dtype=torch.float32, device=A.device)
+    evecs = torch.empty((batch, n, n), dtype=torch.float32, device=A.device) if want_vectors else None
+    offdiag = torch.empty((batch, n), dtype=torch.float32, device=A.device)
+    red = torch.empty((batch,), dtype=torch.int32, device=A.device)
+    st = lib.bed_syevd_lockstep(_ptr(A), batch, n, float(epsilon), iterations, 1 if uniform else 0, _ptr(evals),
+                                _ptr(evecs), _ptr(offdiag), _ptr(red), _ptr(workspace),
+                                workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != 0:
+        raise BedError(st, "bed_syevd_lockstep")
+    return evals, evecs, offdiag, red
 
 
 BED_FN_SQRT = 0

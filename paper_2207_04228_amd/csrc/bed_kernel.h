@@ -46,6 +46,26 @@ struct GradArgs {
 
 hipError_t launch_grad(const GradArgs& args, hipStream_t stream);
 
+// The paper's fixed-budget procedure (bed_lockstep.hip).
+struct LockstepArgs {
+    const float* A;      // [batch][n][n]
+    float* evals;        // [batch][n]
+    float* evecs;        // [batch][n][n] or nullptr; holds P, then V between the launches
+    float* offdiag;      // [batch][n] or nullptr
+    int* reductions;     // [batch] or nullptr
+    float* d;            // workspace [batch][n]
+    float* e;            // workspace [batch][n]
+    int* flags;          // workspace [iterations]: matrices that did not pass the test after iteration i
+    int* window;         // workspace [batch]: window size per matrix (per-matrix rule)
+    int batch;
+    int n;
+    int iterations;
+    int uniform;         // 1: the window is shared by the batch
+    float epsilon;
+};
+
+hipError_t launch_lockstep(const LockstepArgs& args, hipStream_t stream);
+
 // Enqueue one launch; returns hipGetLastError() of the launch.
 hipError_t launch(const KernelArgs& args, int stage, bool want_v, hipStream_t stream);
 

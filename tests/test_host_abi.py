@@ -28,14 +28,14 @@ def _declared_symbols():
 
 def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
-    assert {"bed_syevd", "bed_syevd_info", "bed_tridiag", "bed_tridiag_qr", "bed_tridiag_qr_sweeps", "bed_spd_fn", "bed_syevd_backward", "bed_spd_fn_backward",
+    assert {"bed_syevd", "bed_syevd_info", "bed_tridiag", "bed_tridiag_qr", "bed_tridiag_qr_sweeps", "bed_spd_fn", "bed_syevd_backward", "bed_spd_fn_backward", "bed_syevd_lockstep", "bed_syevd_lockstep_workspace",
             "bed_status_string", "bed_version"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
 
 
 def test_version_and_status_strings(lib):
-    assert binding.bed_version() == 300
+    assert binding.bed_version() == 400
     assert binding.bed_status_string(0) == "BED_OK"
     for code in (-1, -2, -3, -4, -5, -6, -7):
         assert binding.bed_status_string(code).startswith("BED_ERR_")
@@ -90,6 +90,21 @@ def test_argument_validation_is_host_side(lib):
     assert lib.bed_spd_fn_backward(L, V, A, 1, 4, 3, f(1.0), O, None) == -7
     assert lib.bed_spd_fn_backward(L, V, A, 1, 4, 0, f(0.0), A, None) == -6
     assert lib.bed_spd_fn_backward(L, V, A, 0, 4, 0, f(0.0), O, None) == 0
+    # the fixed-budget procedure: workspace size and argument checks (nothing is launched)
+    sz = ctypes.c_size_t
+    need = lib.bed_syevd_lockstep_workspace(8, 16, 16)
+    assert need >= 4 * (2 * 8 * 16 + 16 + 8) and need % 256 == 0
+    assert lib.bed_syevd_lockstep_workspace(8, 65, 16) == 0
+    W = p(0x800000)
+    assert lib.bed_syevd_lockstep(A, 8, 65, f(1e-5), 16, 1, L, V, None, None, W, sz(1 << 20), None) == -3
+    assert lib.bed_syevd_lockstep(A, 8, 16, f(1e-5), -1, 1, L, V, None, None, W, sz(need), None) == -7
+    assert lib.bed_syevd_lockstep(A, 8, 16, f(1e-5), 16, 2, L, V, None, None, W, sz(need), None) == -7
+    assert lib.bed_syevd_lockstep(A, 8, 16, f(float("nan")), 16, 1, L, V, None, None, W, sz(need), None) == -7
+    assert lib.bed_syevd_lockstep(A, 8, 16, f(1e-5), 16, 1, L, V, None, None, None, sz(need), None) == -1
+    assert lib.bed_syevd_lockstep(A, 8, 16, f(1e-5), 16, 1, L, V, None, None, W, sz(need - 256), None) == -7
+    assert lib.bed_syevd_lockstep(A, 8, 16, f(1e-5), 16, 1, L, L, None, None, W, sz(need), None) == -6
+    assert lib.bed_syevd_lockstep(A, 8, 16, f(1e-5), 16, 1, L, V, None, None, p(0x30000), sz(need), None) == -6
+    assert lib.bed_syevd_lockstep(A, 0, 16, f(1e-5), 16, 1, L, V, None, None, W, sz(need), None) == 0
 
 
 def test_binding_rejects_cpu_tensors():

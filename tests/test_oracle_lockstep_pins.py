@@ -132,7 +132,7 @@ def test_reduction_times_in_the_range_the_paper_reports():
 # ---- planted mistakes: each must trip one of the pins above --------------------------------
 
 def test_mutation_transposed_rotation_is_caught(monkeypatch):
-    def bad_qr_step(T, m, mu):
+    def bad_qr_step(T, m, mu, pivots=None):
         M = T[:m, :m] - mu * np.eye(m)
         Q = np.eye(m)
         for k in range(m - 1):
@@ -154,7 +154,7 @@ def test_mutation_transposed_rotation_is_caught(monkeypatch):
 def test_mutation_shift_not_restored_is_caught(monkeypatch):
     good = lockstep.qr_step
 
-    def bad_qr_step(T, m, mu):
+    def bad_qr_step(T, m, mu, pivots=None):
         out, Q = good(T, m, mu)
         out[:m, :m] -= mu * np.eye(m)
         return out, Q
