@@ -284,9 +284,12 @@ def main(argv=None) -> int:
         evb = torch.empty((batch, n), dtype=torch.float32, device=dev)
         Vb = torch.empty((batch, n, n), dtype=torch.float32, device=dev)
         t = timed(lambda: binding.bed_syevd(Ab, evb, Vb), 10)
+        _, _, _, rotb = binding.bed_syevd_info(Ab, evb, Vb)
+        flb = batch * flops_per_matrix(n, float(rotb.float().mean().item()))
         extras["large_batch"][f"n{n}_b{batch}"] = {
             "kernel_us": t * 1e6, "matrices_per_s": batch / t,
-            "gbs": batch * bytes_per_matrix(n) / t / 1e9}
+            "gbs": batch * bytes_per_matrix(n) / t / 1e9,
+            "tflops": flb / t / 1e12, "frac_fp32_valu": flb / t / 1e12 / PEAK_FP32_TFLOPS}
         del Ab, evb, Vb, A32b
 
     dom = per_n["32"]
