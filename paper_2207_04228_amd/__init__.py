@@ -24,3 +24,4 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
 )
+from . import autograd  # noqa: F401,E402  (torch is imported on first use only)
