@@ -324,6 +324,24 @@ def test_workload_generators_are_deterministic_and_symmetric():
     assert np.all(np.sum((rel > 0) & (rel < 2e-6), axis=1) >= 1)
 
 
+def test_structured_cases_are_symmetric_finite_and_known():
+    """The structured inputs of the GPU parity tests, and two of them against their closed
+    forms through the oracle: all-ones has the spectrum {0 (n-1 times), n}; the Wilkinson matrix
+    W_n^+ is symmetric about its anti-diagonal, so its spectrum is that of J W J."""
+    for n in (3, 8, 21):
+        cases = dict(workloads.structured_cases(n, 4, seed=900 + n))
+        again = dict(workloads.structured_cases(n, 4, seed=900 + n))
+        for name, A in cases.items():
+            assert A.dtype == np.float32 and A.shape[1:] == (n, n), name
+            assert np.isfinite(A).all() and np.array_equal(A, A.transpose(0, 2, 1)), name
+            assert np.array_equal(A, again[name]), name
+        lam, _ = jacobi.syevd(cases["all ones"])
+        assert np.abs(lam[:, :-1]).max() <= 1e-12 * n and np.abs(lam[:, -1] - n).max() <= 1e-12 * n
+        W = cases["wilkinson"][0].astype(np.float64)
+        assert np.array_equal(W, W[::-1, ::-1])
+        assert abs(np.trace(W) - jacobi.syevd(cases["wilkinson"])[0][0].sum()) <= 1e-12 * n
+
+
 # --- mutation check: the pins above reject plausible mistakes ------------------
 
 def _battery(solve) -> bool:
