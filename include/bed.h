@@ -26,7 +26,7 @@ extern "C" {
 #endif
 
 #define BED_MAX_N 128
-#define BED_VERSION 400 /* major*10000 + minor*100 + patch: 0.4.0 (0.3.0 + the fixed-budget lock-step procedure) */
+#define BED_VERSION 500 /* major*10000 + minor*100 + patch: 0.5.0 */
 
 typedef enum {
     BED_OK = 0,
@@ -38,6 +38,10 @@ typedef enum {
     BED_ERR_ALIAS = -6,  /* an output buffer overlaps the input             */
     BED_ERR_ARG = -7     /* an enumerated or scalar argument is out of range */
 } bed_status;
+
+/* Fields of the per-matrix `info` word of bed_syevd_info / bed_tridiag_qr / bed_spd_fn. */
+#define BED_INFO_COUNT_MASK 0xFFFF
+#define BED_INFO_RELAXED_SHIFT 16
 
 typedef enum {
     BED_FN_SQRT = 0,     /* f(x) = x^(1/2)                                  */
@@ -69,9 +73,22 @@ int bed_syevd(const float* A, int batch, int n, float* evals, float* evecs,
 
 /*
  * Same as bed_syevd, plus per-matrix diagnostics (either may be NULL):
- *   info       device, [batch] int32: 0 = converged; k > 0 = k off-diagonal
- *              entries of T were still not negligible when the sweep cap was
- *              reached, or k eigenvalues came out non-finite (NaN/Inf input).
+ *   info       device, [batch] int32: 0 = converged to full accuracy.  Otherwise
+ *              info = k + 65536 * w:
+ *              k = info & BED_INFO_COUNT_MASK: k off-diagonal entries of T were
+ *                  still not negligible when the sweep cap was reached, or k
+ *                  eigenvalues came out non-finite (NaN/Inf input);
+ *              w = info >> BED_INFO_RELAXED_SHIFT: w off-diagonal entries were
+ *                  declared negligible only by the fallback test.  The deflation
+ *                  test of Sec. 3.2.3 is relative here,
+ *                  |e_k| <= 4 * 2^-23 (|d_k| + |d_k+1|); a window that has not
+ *                  deflated anything for 12 (24) outer iterations (it sits at
+ *                  the rounding noise of the rotations, which is relative to
+ *                  ||A||, as happens for graded spectra) also accepts
+ *                  |e_k| <= 2^-21 (2^-19) max|a_ij|.  Each such entry
+ *                  perturbs the eigenvalues by at most 2e-6 ||A||_2 (a fifth of
+ *                  the 1e-5 ||A||_2 accuracy bar), but eigenvalues far below
+ *                  ||A||_2 lose their relative accuracy.
  *   rotations  device, [batch] uint32: number of Givens rotations applied to
  *              this matrix (the R of the flop model R*(6n+20); the paper
  *              reports the related "reduction times" in App. C.4).

@@ -15,6 +15,9 @@ _LIB_PATH = os.path.join(_HERE, "libbed.so")
 _lib = None
 
 BED_MAX_N = 128
+# fields of the per-matrix info word (include/bed.h)
+BED_INFO_COUNT_MASK = 0xFFFF
+BED_INFO_RELAXED_SHIFT = 16
 
 
 class BedError(RuntimeError):
@@ -84,14 +87,30 @@ def _stream(stream):
     return ctypes.c_void_p(stream.cuda_stream)
 
 
-def _check_dev(t, name, dtype):
+def _check_dev(t, name, dtype, shape=None, like=None):
+    """A buffer handed to the C ABI: a contiguous CUDA tensor of the given dtype and, where the
+    caller supplied it, of exactly the shape (and on the device) the library will write.  The C
+    side sees raw pointers only, so a smaller, strided or differently typed buffer would become
+    an out-of-bounds device access."""
     import torch
-    if not isinstance(t, torch.Tensor) or not t.is_cuda:
-        raise TypeError(f"{name} must be a CUDA tensor")
+    if not isinstance(t, torch.Tensor):
+        raise TypeError(f"{name} must be a torch.Tensor")
     if t.dtype != dtype:
-        raise TypeError(f"{name} must be {dtype}")
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
     if not t.is_contiguous():
         raise ValueError(f"{name} must be contiguous")
+    if not t.is_cuda:
+        raise TypeError(f"{name} must be a CUDA tensor")
+    if like is not None and t.device != like.device:
+        raise ValueError(f"{name} is on {t.device}, expected {like.device}")
+
+
+def _square_batch(A, name="A"):
+    if A.dim() != 3 or A.shape[1] != A.shape[2]:
+        raise ValueError(f"{name} must be [batch, n, n]")
+    return int(A.shape[0]), int(A.shape[1])
 
 
 def bed_syevd(A, evals=None, evecs=None, *, want_vectors=True, stream=None):
@@ -100,16 +119,16 @@ def bed_syevd(A, evals=None, evecs=None, *, want_vectors=True, stream=None):
     evecs [batch, n, n] with eigenvectors as columns, or None)."""
     import torch
     _check_dev(A, "A", torch.float32)
-    batch, n, n2 = A.shape
-    if n != n2:
-        raise ValueError("A must be [batch, n, n]")
+    batch, n = _square_batch(A)
     if evals is None:
         evals = torch.empty((batch, n), dtype=torch.float32, device=A.device)
     if evecs is None and want_vectors:
         evecs = torch.empty((batch, n, n), dtype=torch.float32, device=A.device)
-    _check_dev(evals, "evals", torch.float32)
+    if not want_vectors:
+        evecs = None
+    _check_dev(evals, "evals", torch.float32, (batch, n), A)
     if evecs is not None:
-        _check_dev(evecs, "evecs", torch.float32)
+        _check_dev(evecs, "evecs", torch.float32, (batch, n, n), A)
     st = load_library().bed_syevd(_ptr(A), batch, n, _ptr(evals), _ptr(evecs), _stream(stream))
     if st != 0:
         raise BedError(st, "bed_syevd")
@@ -120,13 +139,16 @@ def bed_syevd_info(A, evals=None, evecs=None, *, want_vectors=True, stream=None)
     """bed_syevd plus (info int32 [batch], rotations int32-view of uint32 [batch])."""
     import torch
     _check_dev(A, "A", torch.float32)
-    batch, n, n2 = A.shape
-    if n != n2:
-        raise ValueError("A must be [batch, n, n]")
+    batch, n = _square_batch(A)
     if evals is None:
         evals = torch.empty((batch, n), dtype=torch.float32, device=A.device)
     if evecs is None and want_vectors:
         evecs = torch.empty((batch, n, n), dtype=torch.float32, device=A.device)
+    if not want_vectors:
+        evecs = None
+    _check_dev(evals, "evals", torch.float32, (batch, n), A)
+    if evecs is not None:
+        _check_dev(evecs, "evecs", torch.float32, (batch, n, n), A)
     info = torch.empty((batch,), dtype=torch.int32, device=A.device)
     rot = torch.empty((batch,), dtype=torch.int32, device=A.device)
     st = load_library().bed_syevd_info(_ptr(A), batch, n, _ptr(evals), _ptr(evecs),
@@ -140,9 +162,7 @@ def bed_tridiag(A, *, want_P=True, stream=None):
     """Householder tridiagonalisation.  Returns (d [batch,n], e [batch,n], P or None)."""
     import torch
     _check_dev(A, "A", torch.float32)
-    batch, n, n2 = A.shape
-    if n != n2:
-        raise ValueError("A must be [batch, n, n]")
+    batch, n = _square_batch(A)
     d = torch.empty((batch, n), dtype=torch.float32, device=A.device)
     e = torch.empty((batch, n), dtype=torch.float32, device=A.device)
     P = torch.empty((batch, n, n), dtype=torch.float32, device=A.device) if want_P else None
@@ -157,9 +177,10 @@ def bed_tridiag_qr(d, e, *, want_vectors=True, stream=None):
     import torch
     _check_dev(d, "d", torch.float32)
     _check_dev(e, "e", torch.float32)
+    if d.dim() != 2:
+        raise ValueError("d must be [batch, n]")
     batch, n = d.shape
-    if tuple(e.shape) != (batch, n):
-        raise ValueError("e must be [batch, n] (last entry of each row ignored)")
+    _check_dev(e, "e", torch.float32, (batch, n), d)
     evals = torch.empty((batch, n), dtype=torch.float32, device=d.device)
     evecs = torch.empty((batch, n, n), dtype=torch.float32, device=d.device) if want_vectors else None
     info = torch.empty((batch,), dtype=torch.int32, device=d.device)
@@ -176,9 +197,10 @@ def bed_tridiag_qr_sweeps(d, e, sweeps, *, stream=None):
     import torch
     _check_dev(d, "d", torch.float32)
     _check_dev(e, "e", torch.float32)
+    if d.dim() != 2:
+        raise ValueError("d must be [batch, n]")
     batch, n = d.shape
-    if tuple(e.shape) != (batch, n):
-        raise ValueError("e must be [batch, n] (last entry of each row ignored)")
+    _check_dev(e, "e", torch.float32, (batch, n), d)
     d_out = torch.empty_like(d)
     e_out = torch.empty_like(e)
     Q = torch.empty((batch, n, n), dtype=torch.float32, device=d.device)
@@ -197,14 +219,13 @@ def bed_syevd_lockstep(A, epsilon=1e-5, iterations=None, uniform=True, *, want_v
     Returns (evals, evecs or None, offdiag [batch, n], reductions int32 [batch])."""
     import torch
     _check_dev(A, "A", torch.float32)
-    batch, n, n2 = A.shape
-    if n != n2:
-        raise ValueError("A must be [batch, n, n]")
+    batch, n = _square_batch(A)
     iterations = n if iterations is None else int(iterations)
     lib = load_library()
     need = int(lib.bed_syevd_lockstep_workspace(batch, n, iterations))
     if workspace is None:
         workspace = torch.empty((max(need, 4) // 4,), dtype=torch.int32, device=A.device)
+    _check_dev(workspace, "workspace", torch.int32, None, A)     # its size is checked by the library
     evals = torch.empty((batch, n), dtype=torch.float32, device=A.device)
     evecs = torch.empty((batch, n, n), dtype=torch.float32, device=A.device) if want_vectors else None
     offdiag = torch.empty((batch, n), dtype=torch.float32, device=A.device)
@@ -226,12 +247,10 @@ def bed_spd_fn(A, fn, floor, out=None, *, want_evals=False, stream=None):
     Returns (out [batch, n, n], evals or None, info int32 [batch])."""
     import torch
     _check_dev(A, "A", torch.float32)
-    batch, n, n2 = A.shape
-    if n != n2:
-        raise ValueError("A must be [batch, n, n]")
+    batch, n = _square_batch(A)
     if out is None:
         out = torch.empty((batch, n, n), dtype=torch.float32, device=A.device)
-    _check_dev(out, "out", torch.float32)
+    _check_dev(out, "out", torch.float32, (batch, n, n), A)
     evals = torch.empty((batch, n), dtype=torch.float32, device=A.device) if want_evals else None
     info = torch.empty((batch,), dtype=torch.int32, device=A.device)
     st = load_library().bed_spd_fn(_ptr(A), batch, n, int(fn), float(floor), _ptr(out), _ptr(evals),
@@ -251,17 +270,14 @@ def bed_syevd_backward(evals, evecs, grad_evals=None, grad_evecs=None, *, mode=B
     import torch
     _check_dev(evals, "evals", torch.float32)
     _check_dev(evecs, "evecs", torch.float32)
-    batch, n, n2 = evecs.shape
-    if n != n2 or tuple(evals.shape) != (batch, n):
-        raise ValueError("evals must be [batch, n] and evecs [batch, n, n]")
+    batch, n = _square_batch(evecs, "evecs")
+    _check_dev(evals, "evals", torch.float32, (batch, n), evecs)
     for t, name, shape in ((grad_evals, "grad_evals", (batch, n)), (grad_evecs, "grad_evecs", (batch, n, n))):
         if t is not None:
-            _check_dev(t, name, torch.float32)
-            if tuple(t.shape) != shape:
-                raise ValueError(f"{name} must have shape {shape}")
+            _check_dev(t, name, torch.float32, shape, evecs)
     if grad_A is None:
         grad_A = torch.empty((batch, n, n), dtype=torch.float32, device=evecs.device)
-    _check_dev(grad_A, "grad_A", torch.float32)
+    _check_dev(grad_A, "grad_A", torch.float32, (batch, n, n), evecs)
     st = load_library().bed_syevd_backward(_ptr(evals), _ptr(evecs), _ptr(grad_evals), _ptr(grad_evecs), batch, n,
                                            int(mode), int(degree), float(gap_floor), _ptr(grad_A), _stream(stream))
     if st != 0:
@@ -275,12 +291,12 @@ def bed_spd_fn_backward(evals, evecs, grad_out, fn, floor, *, grad_A=None, strea
     _check_dev(evals, "evals", torch.float32)
     _check_dev(evecs, "evecs", torch.float32)
     _check_dev(grad_out, "grad_out", torch.float32)
-    batch, n, n2 = evecs.shape
-    if n != n2 or tuple(evals.shape) != (batch, n) or tuple(grad_out.shape) != (batch, n, n):
-        raise ValueError("evals must be [batch, n]; evecs and grad_out [batch, n, n]")
+    batch, n = _square_batch(evecs, "evecs")
+    _check_dev(evals, "evals", torch.float32, (batch, n), evecs)
+    _check_dev(grad_out, "grad_out", torch.float32, (batch, n, n), evecs)
     if grad_A is None:
         grad_A = torch.empty((batch, n, n), dtype=torch.float32, device=evecs.device)
-    _check_dev(grad_A, "grad_A", torch.float32)
+    _check_dev(grad_A, "grad_A", torch.float32, (batch, n, n), evecs)
     st = load_library().bed_spd_fn_backward(_ptr(evals), _ptr(evecs), _ptr(grad_out), batch, n, int(fn),
                                             float(floor), _ptr(grad_A), _stream(stream))
     if st != 0:

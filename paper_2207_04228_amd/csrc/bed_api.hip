@@ -27,6 +27,50 @@ int run(const bed::KernelArgs& args, int stage, bool want_v, void* stream) {
     return err == hipSuccess ? BED_OK : BED_ERR_LAUNCH;
 }
 
+int lockstep_checked(const float* A, int batch, int n, float epsilon, int iterations, int uniform, float* evals,
+                     float* evecs, float* offdiag, int* reductions, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+    int st = check_common(batch, n);
+    if (st != BED_OK) return st;
+    if (n > 64) return BED_ERR_N;
+    if (iterations < 0 || (uniform != 0 && uniform != 1)) return BED_ERR_ARG;
+    if (!(epsilon >= 0.f) || !(epsilon < __builtin_inff())) return BED_ERR_ARG;
+    if (batch == 0) return BED_OK;
+    if (!A || !evals || !workspace) return BED_ERR_NULL;
+    if (misaligned(A) || misaligned(evals) || misaligned(evecs) || misaligned(offdiag) || misaligned(reductions) ||
+        misaligned(workspace))
+        return BED_ERR_ALIGN;
+    const size_t need = bed_syevd_lockstep_workspace(batch, n, iterations);
+    if (workspace_bytes < need) return BED_ERR_ARG;
+    const size_t mat = (size_t)batch * n * n * sizeof(float), vec = (size_t)batch * n * sizeof(float);
+    const size_t cnt = (size_t)batch * sizeof(int);
+    if (overlaps(A, mat, evals, vec) || overlaps(A, mat, evecs, mat) || overlaps(A, mat, offdiag, vec) ||
+        overlaps(A, mat, reductions, cnt) || overlaps(A, mat, workspace, need) || overlaps(evals, vec, evecs, mat) ||
+        overlaps(evals, vec, offdiag, vec) || overlaps(evals, vec, reductions, cnt) ||
+        overlaps(evals, vec, workspace, need) || overlaps(evecs, mat, offdiag, vec) ||
+        overlaps(evecs, mat, reductions, cnt) || overlaps(evecs, mat, workspace, need) ||
+        overlaps(offdiag, vec, reductions, cnt) || overlaps(offdiag, vec, workspace, need) ||
+        overlaps(reductions, cnt, workspace, need))
+        return BED_ERR_ALIAS;
+    bed::LockstepArgs args{};
+    args.A = A;
+    args.evals = evals;
+    args.evecs = evecs;
+    args.offdiag = offdiag;
+    args.reductions = reductions;
+    float* ws = static_cast<float*>(workspace);
+    args.d = ws;
+    args.e = ws + (size_t)batch * n;
+    args.flags = reinterpret_cast<int*>(ws + 2 * (size_t)batch * n);
+    args.window = args.flags + iterations;
+    args.batch = batch;
+    args.n = n;
+    args.iterations = iterations;
+    args.uniform = uniform;
+    args.epsilon = epsilon;
+    return bed::launch_lockstep(args, static_cast<hipStream_t>(stream)) == hipSuccess ? BED_OK : BED_ERR_LAUNCH;
+}
+
 }  // namespace
 
 extern "C" {
@@ -220,45 +264,8 @@ size_t bed_syevd_lockstep_workspace(int batch, int n, int iterations) {
 int bed_syevd_lockstep(const float* A, int batch, int n, float epsilon, int iterations, int uniform, float* evals,
                        float* evecs, float* offdiag, int* reductions, void* workspace, size_t workspace_bytes,
                        void* stream) {
-    int st = check_common(batch, n);
-    if (st != BED_OK) return st;
-    if (n > 64) return BED_ERR_N;
-    if (iterations < 0 || (uniform != 0 && uniform != 1)) return BED_ERR_ARG;
-    if (!(epsilon >= 0.f) || !(epsilon < __builtin_inff())) return BED_ERR_ARG;
-    if (batch == 0) return BED_OK;
-    if (!A || !evals || !workspace) return BED_ERR_NULL;
-    if (misaligned(A) || misaligned(evals) || misaligned(evecs) || misaligned(offdiag) || misaligned(reductions) ||
-        misaligned(workspace))
-        return BED_ERR_ALIGN;
-    const size_t need = bed_syevd_lockstep_workspace(batch, n, iterations);
-    if (workspace_bytes < need) return BED_ERR_ARG;
-    const size_t mat = (size_t)batch * n * n * sizeof(float), vec = (size_t)batch * n * sizeof(float);
-    const size_t cnt = (size_t)batch * sizeof(int);
-    if (overlaps(A, mat, evals, vec) || overlaps(A, mat, evecs, mat) || overlaps(A, mat, offdiag, vec) ||
-        overlaps(A, mat, reductions, cnt) || overlaps(A, mat, workspace, need) || overlaps(evals, vec, evecs, mat) ||
-        overlaps(evals, vec, offdiag, vec) || overlaps(evals, vec, reductions, cnt) ||
-        overlaps(evals, vec, workspace, need) || overlaps(evecs, mat, offdiag, vec) ||
-        overlaps(evecs, mat, reductions, cnt) || overlaps(evecs, mat, workspace, need) ||
-        overlaps(offdiag, vec, reductions, cnt) || overlaps(offdiag, vec, workspace, need) ||
-        overlaps(reductions, cnt, workspace, need))
-        return BED_ERR_ALIAS;
-    bed::LockstepArgs args{};
-    args.A = A;
-    args.evals = evals;
-    args.evecs = evecs;
-    args.offdiag = offdiag;
-    args.reductions = reductions;
-    float* ws = static_cast<float*>(workspace);
-    args.d = ws;
-    args.e = ws + (size_t)batch * n;
-    args.flags = reinterpret_cast<int*>(ws + 2 * (size_t)batch * n);
-    args.window = args.flags + iterations;
-    args.batch = batch;
-    args.n = n;
-    args.iterations = iterations;
-    args.uniform = uniform;
-    args.epsilon = epsilon;
-    return bed::launch_lockstep(args, static_cast<hipStream_t>(stream)) == hipSuccess ? BED_OK : BED_ERR_LAUNCH;
+    return lockstep_checked(A, batch, n, epsilon, iterations, uniform, evals, evecs, offdiag, reductions, workspace,
+                            workspace_bytes, stream);
 }
 
 const char* bed_status_string(int status) {

@@ -306,8 +306,7 @@ __global__ __launch_bounds__(BT) void block_kernel(KernelArgs args) {
 
 template <bool WANT_V, int STAGE>
 hipError_t launch_block_one(const KernelArgs& args, hipStream_t stream) {
-    hipLaunchKernelGGL((block_kernel<WANT_V, STAGE>), dim3(args.batch), dim3(BT), 0, stream, args);
-    return hipGetLastError();
+    return enqueue(block_kernel<WANT_V, STAGE>, dim3(args.batch), dim3(BT), stream, args);
 }
 
 }  // namespace

@@ -245,18 +245,17 @@ hipError_t launch_grad(const GradArgs& args, hipStream_t stream) {
     if (args.batch == 0) return hipSuccess;
     const int n = args.n, B = args.batch;
     if (n <= 4)
-        hipLaunchKernelGGL((grad_kernel<1, 1, 4>), dim3((B + 7) / 8), dim3(64), 0, stream, args);
+        return enqueue(grad_kernel<1, 1, 4>, dim3((B + 7) / 8), dim3(64), stream, args);
     else if (n <= 8)
-        hipLaunchKernelGGL((grad_kernel<1, 1, 8>), dim3((B + 3) / 4), dim3(64), 0, stream, args);
+        return enqueue(grad_kernel<1, 1, 8>, dim3((B + 3) / 4), dim3(64), stream, args);
     else if (n <= 16)
-        hipLaunchKernelGGL((grad_kernel<1, 1, 16>), dim3((B + 1) / 2), dim3(64), 0, stream, args);
+        return enqueue(grad_kernel<1, 1, 16>, dim3((B + 1) / 2), dim3(64), stream, args);
     else if (n <= 32)
-        hipLaunchKernelGGL((grad_kernel<1, 1, 0>), dim3(B), dim3(64), 0, stream, args);
+        return enqueue(grad_kernel<1, 1, 0>, dim3(B), dim3(64), stream, args);
     else if (n <= 64)
-        hipLaunchKernelGGL((grad_kernel<2, 1, 0>), dim3(B), dim3(64), 0, stream, args);
+        return enqueue(grad_kernel<2, 1, 0>, dim3(B), dim3(64), stream, args);
     else
-        hipLaunchKernelGGL((grad_kernel<4, 4, 0>), dim3(B), dim3(256), 0, stream, args);
-    return hipGetLastError();
+        return enqueue(grad_kernel<4, 4, 0>, dim3(B), dim3(256), stream, args);
 }
 
 }  // namespace bed

@@ -7,6 +7,19 @@
 
 namespace bed {
 
+// Launches `kernel` and returns the status of THIS launch.  (Reading hipGetLastError() after a
+// triple-chevron launch would also report, and consume, an error left behind by an unrelated
+// earlier HIP call of the calling thread.)
+template <typename T>
+struct same_type { using type = T; };
+
+template <typename... KArgs>
+inline hipError_t enqueue(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t stream,
+                          typename same_type<KArgs>::type... args) {
+    void* argv[] = {const_cast<void*>(static_cast<const void*>(&args))...};
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, argv, 0, stream);
+}
+
 enum Stage { kFull = 0, kTridiagOnly = 1, kQrOnly = 2, kSpectral = 3, kQrPartial = 4 };
 enum SpectralFn { kFnSqrt = 0, kFnInvSqrt = 1 };
 
@@ -66,7 +79,7 @@ struct LockstepArgs {
 
 hipError_t launch_lockstep(const LockstepArgs& args, hipStream_t stream);
 
-// Enqueue one launch; returns hipGetLastError() of the launch.
+// Enqueue one launch; returns the status of that launch.
 hipError_t launch(const KernelArgs& args, int stage, bool want_v, hipStream_t stream);
 
 }  // namespace bed

@@ -207,12 +207,12 @@ hipError_t launch_lockstep(const LockstepArgs& a, hipStream_t stream) {
     hipError_t err = launch(t, kTridiagOnly, a.evecs != nullptr, stream);
     if (err != hipSuccess) return err;
     const int items = a.batch > a.iterations ? a.batch : a.iterations;
-    hipLaunchKernelGGL(lockstep_init, dim3((items + 255) / 256), dim3(256), 0, stream, a.flags, a.iterations,
-                       a.window, a.batch, a.n);
-    for (int it = 0; it < a.iterations; ++it)
-        hipLaunchKernelGGL(lockstep_iteration, dim3(a.batch), dim3(64), 0, stream, a, it);
-    hipLaunchKernelGGL(lockstep_finish, dim3(a.batch), dim3(64), 0, stream, a);
-    return hipGetLastError();
+    err = enqueue(lockstep_init, dim3((items + 255) / 256), dim3(256), stream, a.flags, a.iterations, a.window,
+                  a.batch, a.n);
+    for (int it = 0; it < a.iterations && err == hipSuccess; ++it)
+        err = enqueue(lockstep_iteration, dim3(a.batch), dim3(64), stream, a, it);
+    if (err != hipSuccess) return err;
+    return enqueue(lockstep_finish, dim3(a.batch), dim3(64), stream, a);
 }
 
 }  // namespace bed

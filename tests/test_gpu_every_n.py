@@ -13,6 +13,7 @@ def test_every_n(first):
     from oracle.acceptance import evaluate
     from paper_2207_04228_amd import binding, workloads
     worst = dict(eval_err=0.0, residual=0.0, orth=0.0, angle=0.0)
+    relaxed = []      # (n, kind, count): off-diagonals deflated only by the fallback test (upper half of info)
     for n in range(first, first + 32):
         rng = np.random.default_rng(5000 + n)
         batch = 12 if n <= 64 else 5
@@ -27,8 +28,13 @@ def test_every_n(first):
             lam_o, V_o = jacobi.syevd(A)
             acc = evaluate(A, ev.cpu().numpy(), V.cpu().numpy(), lam_o, V_o)
             w = acc.worst()
-            assert acc.passes() and int(info.max()) == 0, (n, kind, w)
+            assert acc.passes() and int((info & 0xFFFF).max()) == 0, (n, kind, w)
+            if int((info >> 16).sum()):
+                relaxed.append((n, kind, int((info >> 16).sum())))
             for key in worst:
                 worst[key] = max(worst[key], w[key] / (n if key in ("residual", "orth") else 1))
     print(f"[every n] {first}..{first + 31}: worst eval {worst['eval_err']:.2e}, residual/n {worst['residual']:.2e}, "
-          f"orth/n {worst['orth']:.2e}, angle {worst['angle']:.2e}", flush=True)
+          f"orth/n {worst['orth']:.2e}, angle {worst['angle']:.2e}; "
+          f"fallback deflations (n, kind, count): {relaxed}", flush=True)
+    # the fallback is for spectra graded over many orders of magnitude (kind 4) and rank-deficient input (kind 0)
+    assert all(kind in (0, 4) for _, kind, _ in relaxed), relaxed

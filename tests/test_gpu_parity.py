@@ -71,9 +71,13 @@ def test_config3(n):
     _check(workloads.config3(n), f"config3_n{n}")
 
 
-def test_config4_sample():
+def test_config4():
+    """Config 4 at its stated size: 4096 matrices of 16 x 16, Haar Q, lambda_i = i^-2 (the
+    whitening-like spectrum of Sec. 4.2 / App. B.1), every matrix against the oracle."""
     from paper_2207_04228_amd import workloads
-    _check(workloads.config4(batch=1024), "config4_b1024")
+    A = workloads.config4()
+    assert A.shape == (4096, 16, 16)
+    _check(A, "config4_b4096")
 
 
 @pytest.mark.parametrize("n", [48, 64])
@@ -161,6 +165,107 @@ def test_eigenvalues_only_matches_full_path():
         lam_only, V = _solve_gpu(A, want_vectors=False)
         assert V is None
         assert np.array_equal(lam_full, lam_only)
+
+
+def _check_eigenvalues_only(A32, name):
+    """evecs = NULL (the economic eigenvalue calculation of Sec. 3.2.4) against the ORACLE:
+    ascending, finite, within 1e-5 ||A||_2 of the Jacobi eigenvalues, info = 0, and the
+    trace / Frobenius identities of the spectrum."""
+    from oracle import jacobi
+    print(f"[parity] {name} eigenvalues only, shape={A32.shape}", flush=True)
+    lam_o, _ = jacobi.syevd(A32)
+    lam_g, V, info, rot = _solve_gpu(A32, want_vectors=False, info=True)
+    assert V is None
+    assert np.isfinite(lam_g).all()
+    assert np.all(np.diff(lam_g, axis=1) >= 0), "eigenvalues not ascending"
+    assert np.all(info == 0)
+    norm2 = np.maximum(np.abs(lam_o).max(axis=1), 1e-300)
+    err = (np.abs(lam_g.astype(np.float64) - lam_o).max(axis=1) / norm2).max()
+    print(f"[parity] {name} eigenvalues only: eval {err:.2e}", flush=True)
+    assert err <= EVAL_TOL
+    n = A32.shape[-1]
+    A64 = np.tril(A32.astype(np.float64))
+    A64 = A64 + np.tril(A64, -1).transpose(0, 2, 1)
+    fro2 = (A64 * A64).sum(axis=(1, 2))
+    assert np.all(np.abs(lam_g.astype(np.float64).sum(axis=1) - np.trace(A64, axis1=1, axis2=2))
+                  <= 1e-5 * n * np.sqrt(fro2))
+
+
+@pytest.mark.parametrize("n", [16, 32, 48])
+def test_eigenvalues_only_against_oracle_wave_kernel(n):
+    from paper_2207_04228_amd import workloads
+    A = workloads.config3(n, batch=512) if n <= 32 else workloads.config5(n)
+    _check_eigenvalues_only(A, f"wave_n{n}")
+
+
+def test_eigenvalues_only_against_oracle_config4():
+    from paper_2207_04228_amd import workloads
+    _check_eigenvalues_only(workloads.config4(), "config4_b4096")
+
+
+def test_eigenvalues_only_against_oracle_block_kernel():
+    rng = np.random.default_rng(4100)
+    A = rng.standard_normal((24, 100, 100))
+    A = (0.5 * (A + A.transpose(0, 2, 1))).astype(np.float32)
+    _check_eigenvalues_only(A, "block_n100")
+
+
+@pytest.mark.parametrize("n,batch", [(4, 6144), (4, 6144 + 64 + 21), (3, 7001), (8, 12288), (8, 12288 + 128 + 5),
+                                     (6, 13003)])
+def test_eigenvalues_only_against_oracle_lane_kernel(n, batch):
+    """evecs = NULL at the batch sizes that dispatch to the one-matrix-per-lane kernels
+    (n <= 4 from batch 6144, n <= 8 from batch 12288), full and ragged last wavefronts."""
+    from paper_2207_04228_amd import workloads
+    if n == 4:
+        A = workloads.config2(65536)[:batch]
+    elif n == 8:
+        A = workloads.config3(8, batch=batch)
+    else:
+        rng = np.random.default_rng(4200 + n)
+        A = rng.standard_normal((batch, n, n))
+        A = (0.5 * (A + A.transpose(0, 2, 1))).astype(np.float32)
+    _check_eigenvalues_only(np.ascontiguousarray(A), f"lane_n{n}_b{batch}")
+
+
+def test_no_fallback_deflation_on_the_five_configs():
+    """A window that stalls also deflates entries below an absolute threshold (counted in the upper half of
+    info).  On the five workloads this must never happen: info is exactly 0 for every matrix."""
+    from paper_2207_04228_amd import workloads
+    cases = [("config1", workloads.config1())]
+    cases += [(f"config2_b{b}", workloads.config2(b)) for b in (256, 512, 4096, 65536)]
+    cases += [(f"config3_n{n}", workloads.config3(n)) for n in (8, 16, 24, 32)]
+    cases += [("config4", workloads.config4())]
+    cases += [(f"config5_n{n}", workloads.config5(n)) for n in (48, 64)]
+    for name, A in cases:
+        for want_v in (True, False):
+            _, _, info, _ = _solve_gpu(A, want_vectors=want_v, info=True)
+            assert np.all(info == 0), (name, want_v, int((info >> 16).sum()), int((info & 0xFFFF).sum()))
+
+
+def test_binding_rejects_mismatched_output_buffers():
+    """Every caller-supplied buffer is checked against A's shape, dtype, layout and device before
+    its pointer reaches the library."""
+    import torch
+    from paper_2207_04228_amd import binding, workloads
+    dev = torch.device("cuda:0")
+    A = torch.from_numpy(workloads.config3(8, batch=16)).to(dev)
+    ev = torch.empty((16, 8), dtype=torch.float32, device=dev)
+    V = torch.empty((16, 8, 8), dtype=torch.float32, device=dev)
+    for bad_ev, bad_V, exc in ((ev[:8], V, ValueError), (ev.double(), V, TypeError), (ev, V[:, :, :4], ValueError),
+                               (ev, V.transpose(1, 2), ValueError), (ev, V.double(), TypeError),
+                               (ev.cpu(), V, TypeError)):
+        with pytest.raises(exc):
+            binding.bed_syevd(A, bad_ev, bad_V)
+        with pytest.raises(exc):
+            binding.bed_syevd_info(A, bad_ev, bad_V)
+    with pytest.raises(ValueError):
+        binding.bed_spd_fn(A, binding.BED_FN_SQRT, 0.0, out=V[:8])
+    with pytest.raises(ValueError):
+        binding.bed_syevd_backward(ev, V, ev, V, grad_A=V[:8])
+    with pytest.raises(ValueError):
+        binding.bed_spd_fn_backward(ev, V, V, binding.BED_FN_SQRT, 0.0, grad_A=V[:, :4])
+    binding.bed_syevd(A, ev, V)                      # the matching buffers are accepted
+    torch.cuda.synchronize()
 
 
 def test_info_and_rotation_counts():

@@ -22,6 +22,7 @@ def test_repeated_eigenvalues_converge(n):
     from oracle.acceptance import evaluate
     from paper_2207_04228_amd import binding, workloads
     worst_rot = 0.0
+    relaxed, matrices = 0, 0   # off-diagonals deflated only by the fallback test (upper half of info)
     for seed in (1, 2, 6, 10):                       # seeds that used to stall are among them
         rng = np.random.default_rng(7000 + 100 * n + seed)
         batch = 48 if n <= 64 else 16
@@ -29,12 +30,15 @@ def test_repeated_eigenvalues_converge(n):
             A = workloads.from_spectrum(lam, seed=seed * 7 + kind)
             ev, V, info, rot = binding.bed_syevd_info(torch.from_numpy(A).to("cuda:0"))
             torch.cuda.synchronize()
-            assert int(info.max()) == 0, (n, seed, kind)
+            assert int((info & 0xFFFF).max()) == 0, (n, seed, kind)
+            relaxed += int((info >> 16).sum())
+            matrices += int((info >> 16 > 0).sum())
             worst_rot = max(worst_rot, int(rot.max()) / (n * n))
             lam_o, V_o = jacobi.syevd(A)
             acc = evaluate(A, ev.cpu().numpy(), V.cpu().numpy(), lam_o, V_o)
             assert acc.passes(), (n, seed, kind, acc.worst())
-    print(f"[repeated] n={n}: max rotations / n^2 = {worst_rot:.2f}", flush=True)
+    print(f"[repeated] n={n}: max rotations / n^2 = {worst_rot:.2f}; fallback deflations: "
+          f"{relaxed} in {matrices} matrices", flush=True)
     assert worst_rot <= 4.0
 
 
@@ -50,6 +54,8 @@ def test_lane_kernel_with_repeated_eigenvalues():
         A = workloads.from_spectrum(lam, seed=n)
         ev, V, info, rot = binding.bed_syevd_info(torch.from_numpy(A).to("cuda:0"))
         torch.cuda.synchronize()
-        assert int(info.max()) == 0 and int(rot.max()) <= 6 * n * n
+        assert int((info & 0xFFFF).max()) == 0 and int(rot.max()) <= 6 * n * n
+        print(f"[repeated] lane kernel n={n}: fallback deflations: {int((info >> 16).sum())}",
+              flush=True)
         lam_o, V_o = jacobi.syevd(A)
         assert evaluate(A, ev.cpu().numpy(), V.cpu().numpy(), lam_o, V_o).passes()

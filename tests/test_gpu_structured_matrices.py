@@ -15,10 +15,12 @@ def test_structured_matrices(n):
     from paper_2207_04228_amd import binding, workloads
     batch = 16 if n <= 64 else 4
     worst = {"eval_err": 0.0, "residual": 0.0, "orth": 0.0}
+    relaxed = 0       # off-diagonals deflated only by the fallback test (upper half of info)
     for name, A in workloads.structured_cases(n, batch, seed=900 + n):
         ev, V, info, rot = binding.bed_syevd_info(torch.from_numpy(A).to("cuda:0"))
         torch.cuda.synchronize()
-        assert int(info.max()) == 0, (n, name)
+        assert int((info & 0xFFFF).max()) == 0, (n, name)
+        relaxed += int((info >> 16).sum())
         assert int(rot.max()) <= 4 * n * n + 8, (n, name, int(rot.max()))
         lam_o, V_o = jacobi.syevd(A)
         acc = evaluate(A, ev.cpu().numpy(), V.cpu().numpy(), lam_o, V_o)
@@ -26,7 +28,8 @@ def test_structured_matrices(n):
         assert acc.passes(), (n, name, w)
         for k in worst:
             worst[k] = max(worst[k], w[k])
-    print(f"[structured] n={n}: eval {worst['eval_err']:.2e} res {worst['residual']:.2e} orth {worst['orth']:.2e}", flush=True)
+    print(f"[structured] n={n}: eval {worst['eval_err']:.2e} res {worst['residual']:.2e} orth {worst['orth']:.2e}; "
+          f"fallback deflations: {relaxed}", flush=True)
 
 
 @pytest.mark.parametrize("batch", [2, 8192])

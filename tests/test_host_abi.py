@@ -35,7 +35,7 @@ def test_header_symbols_are_exported(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert binding.bed_version() == 400
+    assert binding.bed_version() == 500
     assert binding.bed_status_string(0) == "BED_OK"
     for code in (-1, -2, -3, -4, -5, -6, -7):
         assert binding.bed_status_string(code).startswith("BED_ERR_")
@@ -111,3 +111,25 @@ def test_binding_rejects_cpu_tensors():
     import torch
     with pytest.raises(TypeError):
         binding.bed_syevd(torch.zeros(2, 4, 4))
+
+
+def test_binding_rejects_mismatched_buffers_before_any_pointer_is_passed():
+    """The C side sees raw pointers only: dtype, shape and contiguity of every buffer are checked
+    by the binding, in that order, before the device check (so this runs without a GPU)."""
+    import torch
+    chk = binding._check_dev
+    good = torch.zeros((3, 4, 4), dtype=torch.float32)
+    with pytest.raises(TypeError, match="float32"):
+        chk(good.double(), "evecs", torch.float32, (3, 4, 4))
+    with pytest.raises(ValueError, match="shape"):
+        chk(torch.zeros((3, 4, 3)), "evecs", torch.float32, (3, 4, 4))
+    with pytest.raises(ValueError, match="shape"):
+        chk(torch.zeros((2, 4, 4)), "evecs", torch.float32, (3, 4, 4))
+    with pytest.raises(ValueError, match="contiguous"):
+        chk(good.transpose(1, 2), "evecs", torch.float32, (3, 4, 4))
+    with pytest.raises(TypeError, match="torch.Tensor"):
+        chk([1.0], "evecs", torch.float32, (1,))
+    with pytest.raises(TypeError, match="CUDA"):       # everything else in order: only the device is wrong
+        chk(good, "evecs", torch.float32, (3, 4, 4))
+    with pytest.raises(ValueError, match=r"\[batch, n, n\]"):
+        binding._square_batch(torch.zeros((3, 4, 5)))
