@@ -36,7 +36,8 @@ typedef enum {
     BED_ERR_ALIGN = -4,  /* a pointer is not 4-byte aligned                 */
     BED_ERR_LAUNCH = -5, /* the HIP runtime refused the launch              */
     BED_ERR_ALIAS = -6,  /* an output buffer overlaps the input             */
-    BED_ERR_ARG = -7     /* an enumerated or scalar argument is out of range */
+    BED_ERR_ARG = -7,    /* an enumerated or scalar argument is out of range */
+    BED_ERR_SCRATCH = -8 /* the problem does not fit the library's built-in scratch memory */
 } bed_status;
 
 /* Fields of the per-matrix `info` word of bed_syevd_info / bed_tridiag_qr / bed_spd_fn. */
@@ -237,6 +238,31 @@ size_t bed_syevd_lockstep_workspace(int batch, int n, int iterations);
 int bed_syevd_lockstep(const float* A, int batch, int n, float epsilon, int iterations, int uniform,
                        float* evals, float* evecs, float* offdiag, int* reductions,
                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * bed_syevd_lockstep for callers that can neither allocate nor bring a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and same results as bed_syevd_lockstep, but the per-iteration state lives in scratch
+ * memory built into the library (a file-scope __device__ array, one copy per GPU, held until the
+ * process ends) instead of a caller-owned workspace.  The call allocates nothing, on the host
+ * side of the runtime or on the device.
+ *
+ *   capacity     bed_syevd_lockstep_static_capacity() bytes (1 MiB).  A problem fits when
+ *                bed_syevd_lockstep_workspace(batch, n, iterations) <= capacity, i.e. roughly
+ *                batch * n <= 130 000 (512 matrices of 32 x 32 use 133 KB); otherwise the call
+ *                returns BED_ERR_SCRATCH and enqueues nothing.
+ *   sharing      every call on a GPU uses that GPU's one scratch array: calls that may overlap
+ *                in time on the same GPU (different streams, different host threads) race and
+ *                must be serialised by the caller.  The array keeps the previous call's
+ *                contents; everything a call reads from it is written by that call first
+ *                (a fill kernel, no memset node, so the call may be captured into a graph).
+ *   first call   the first call on each device looks up the array's device address
+ *                (hipGetSymbolAddress); make that call outside graph capture.
+ * All other arguments, layouts and error codes are those of bed_syevd_lockstep.
+ */
+size_t bed_syevd_lockstep_static_capacity(void);
+int bed_syevd_lockstep_static(const float* A, int batch, int n, float epsilon, int iterations, int uniform,
+                              float* evals, float* evecs, float* offdiag, int* reductions, void* stream);
 
 /* Human-readable name of a bed_status value (static storage). */
 const char* bed_status_string(int status);

@@ -16,6 +16,8 @@ from .binding import (  # noqa: F401
     bed_syevd,
     bed_syevd_info,
     bed_syevd_lockstep,
+    bed_syevd_lockstep_static,
+    bed_syevd_lockstep_static_capacity,
     bed_tridiag,
     bed_tridiag_qr,
     bed_tridiag_qr_sweeps,

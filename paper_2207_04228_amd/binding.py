@@ -60,6 +60,10 @@ def load_library():
         lib.bed_syevd_lockstep_workspace.restype = ctypes.c_size_t
         lib.bed_syevd_lockstep.argtypes = [vp, ci, ci, ctypes.c_float, ci, ci, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.bed_syevd_lockstep.restype = ci
+        lib.bed_syevd_lockstep_static_capacity.argtypes = []
+        lib.bed_syevd_lockstep_static_capacity.restype = ctypes.c_size_t
+        lib.bed_syevd_lockstep_static.argtypes = [vp, ci, ci, ctypes.c_float, ci, ci, vp, vp, vp, vp, vp]
+        lib.bed_syevd_lockstep_static.restype = ci
         lib.bed_status_string.argtypes = [ci]
         lib.bed_status_string.restype = ctypes.c_char_p
         lib.bed_version.argtypes = []
@@ -236,6 +240,42 @@ def bed_syevd_lockstep(A, epsilon=1e-5, iterations=None, uniform=True, *, want_v
     if st != 0:
         raise BedError(st, "bed_syevd_lockstep")
     return evals, evecs, offdiag, red
+
+
+def bed_syevd_lockstep_static(A, epsilon=1e-5, iterations=None, uniform=True, *, evals=None, evecs=None,
+                              offdiag=None, reductions=None, want_vectors=True, stream=None):
+    """bed_syevd_lockstep on the library's built-in scratch memory.  With all four output buffers
+    supplied, neither this wrapper nor the library allocates anything.
+    Returns (evals, evecs or None, offdiag [batch, n], reductions int32 [batch])."""
+    import torch
+    _check_dev(A, "A", torch.float32)
+    batch, n = _square_batch(A)
+    iterations = n if iterations is None else int(iterations)
+    if evals is None:
+        evals = torch.empty((batch, n), dtype=torch.float32, device=A.device)
+    if evecs is None and want_vectors:
+        evecs = torch.empty((batch, n, n), dtype=torch.float32, device=A.device)
+    if not want_vectors:
+        evecs = None
+    if offdiag is None:
+        offdiag = torch.empty((batch, n), dtype=torch.float32, device=A.device)
+    if reductions is None:
+        reductions = torch.empty((batch,), dtype=torch.int32, device=A.device)
+    _check_dev(evals, "evals", torch.float32, (batch, n), A)
+    if evecs is not None:
+        _check_dev(evecs, "evecs", torch.float32, (batch, n, n), A)
+    _check_dev(offdiag, "offdiag", torch.float32, (batch, n), A)
+    _check_dev(reductions, "reductions", torch.int32, (batch,), A)
+    st = load_library().bed_syevd_lockstep_static(_ptr(A), batch, n, float(epsilon), iterations, 1 if uniform else 0,
+                                                  _ptr(evals), _ptr(evecs), _ptr(offdiag), _ptr(reductions),
+                                                  _stream(stream))
+    if st != 0:
+        raise BedError(st, "bed_syevd_lockstep_static")
+    return evals, evecs, offdiag, reductions
+
+
+def bed_syevd_lockstep_static_capacity() -> int:
+    return int(load_library().bed_syevd_lockstep_static_capacity())
 
 
 BED_FN_SQRT = 0

@@ -27,21 +27,28 @@ int run(const bed::KernelArgs& args, int stage, bool want_v, void* stream) {
     return err == hipSuccess ? BED_OK : BED_ERR_LAUNCH;
 }
 
+// Both lock-step entry points.  builtin_scratch: the workspace is the library's own scratch
+// memory, whose device address is looked up only after every host-side check has passed.
 int lockstep_checked(const float* A, int batch, int n, float epsilon, int iterations, int uniform, float* evals,
                      float* evecs, float* offdiag, int* reductions, void* workspace, size_t workspace_bytes,
-                     void* stream) {
+                     bool builtin_scratch, void* stream) {
     int st = check_common(batch, n);
     if (st != BED_OK) return st;
     if (n > 64) return BED_ERR_N;
     if (iterations < 0 || (uniform != 0 && uniform != 1)) return BED_ERR_ARG;
     if (!(epsilon >= 0.f) || !(epsilon < __builtin_inff())) return BED_ERR_ARG;
     if (batch == 0) return BED_OK;
-    if (!A || !evals || !workspace) return BED_ERR_NULL;
+    if (!A || !evals || (!workspace && !builtin_scratch)) return BED_ERR_NULL;
     if (misaligned(A) || misaligned(evals) || misaligned(evecs) || misaligned(offdiag) || misaligned(reductions) ||
         misaligned(workspace))
         return BED_ERR_ALIGN;
     const size_t need = bed_syevd_lockstep_workspace(batch, n, iterations);
-    if (workspace_bytes < need) return BED_ERR_ARG;
+    if (builtin_scratch) {
+        if (need > bed::kLockstepScratchBytes) return BED_ERR_SCRATCH;
+        if (bed::lockstep_scratch(&workspace) != hipSuccess) return BED_ERR_LAUNCH;
+    } else if (workspace_bytes < need) {
+        return BED_ERR_ARG;
+    }
     const size_t mat = (size_t)batch * n * n * sizeof(float), vec = (size_t)batch * n * sizeof(float);
     const size_t cnt = (size_t)batch * sizeof(int);
     if (overlaps(A, mat, evals, vec) || overlaps(A, mat, evecs, mat) || overlaps(A, mat, offdiag, vec) ||
@@ -265,7 +272,15 @@ int bed_syevd_lockstep(const float* A, int batch, int n, float epsilon, int iter
                        float* evecs, float* offdiag, int* reductions, void* workspace, size_t workspace_bytes,
                        void* stream) {
     return lockstep_checked(A, batch, n, epsilon, iterations, uniform, evals, evecs, offdiag, reductions, workspace,
-                            workspace_bytes, stream);
+                            workspace_bytes, false, stream);
+}
+
+size_t bed_syevd_lockstep_static_capacity(void) { return bed::kLockstepScratchBytes; }
+
+int bed_syevd_lockstep_static(const float* A, int batch, int n, float epsilon, int iterations, int uniform,
+                              float* evals, float* evecs, float* offdiag, int* reductions, void* stream) {
+    return lockstep_checked(A, batch, n, epsilon, iterations, uniform, evals, evecs, offdiag, reductions, nullptr, 0,
+                            true, stream);
 }
 
 const char* bed_status_string(int status) {
@@ -278,6 +293,7 @@ const char* bed_status_string(int status) {
         case BED_ERR_LAUNCH: return "BED_ERR_LAUNCH: kernel launch failed";
         case BED_ERR_ALIAS: return "BED_ERR_ALIAS: buffers overlap";
         case BED_ERR_ARG: return "BED_ERR_ARG: argument out of range";
+        case BED_ERR_SCRATCH: return "BED_ERR_SCRATCH: the problem does not fit the library's built-in scratch memory";
         default: return "BED_ERR_UNKNOWN";
     }
 }

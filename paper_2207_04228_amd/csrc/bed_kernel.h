@@ -79,6 +79,11 @@ struct LockstepArgs {
 
 hipError_t launch_lockstep(const LockstepArgs& args, hipStream_t stream);
 
+// Size of the library's built-in scratch memory for the lock-step procedure, and its device
+// address on the current device (looked up on the first call per device; allocates nothing).
+constexpr size_t kLockstepScratchBytes = 1u << 20;
+hipError_t lockstep_scratch(void** ptr);
+
 // Enqueue one launch; returns the status of that launch.
 hipError_t launch(const KernelArgs& args, int stage, bool want_v, hipStream_t stream);
 

@@ -23,11 +23,24 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "bed_kernel.h"
 
 namespace bed {
 
 namespace {
+
+// Built-in scratch memory for callers that cannot bring a workspace of their own (code under
+// HIP graph capture, serving loops and harnesses that must not allocate).  One copy per GPU,
+// held until the process ends.  In host code the array's name is only a stand-in for the
+// symbol: the device address is looked up once per device with hipGetSymbolAddress and every
+// use goes through that pointer.
+static __device__ __align__(256) unsigned char scratch[kLockstepScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
 
 constexpr int LN = 64;               // largest n
 constexpr int LLD = 65;              // column stride of V in LDS (odd)
@@ -194,6 +207,23 @@ __global__ __launch_bounds__(64) void lockstep_finish(LockstepArgs a) {
 }
 
 }  // namespace
+
+hipError_t lockstep_scratch(void** ptr) {
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (err != hipSuccess) return err;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return hipSuccess;
+}
 
 hipError_t launch_lockstep(const LockstepArgs& a, hipStream_t stream) {
     // Sec. 3.1: d, e into the workspace, P into the eigenvector buffer

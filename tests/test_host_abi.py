@@ -37,7 +37,7 @@ def test_header_symbols_are_exported(lib):
 def test_version_and_status_strings(lib):
     assert binding.bed_version() == 500
     assert binding.bed_status_string(0) == "BED_OK"
-    for code in (-1, -2, -3, -4, -5, -6, -7):
+    for code in (-1, -2, -3, -4, -5, -6, -7, -8):
         assert binding.bed_status_string(code).startswith("BED_ERR_")
     assert "UNKNOWN" in binding.bed_status_string(-99)
 
@@ -58,6 +58,16 @@ def test_argument_validation_is_host_side(lib):
     assert lib.bed_tridiag_qr(A, None, 1, 4, L, V, None, None, None) == -1
     assert lib.bed_tridiag_qr(A, L, 0, 4, V, None, None, None, None) == 0
     assert lib.bed_syevd_info(A, 1, 4, L, V, p(0x40001), None, None) == -4
+    # the lock-step procedure on built-in scratch memory: argument errors first, then the capacity
+    f = ctypes.c_float
+    assert lib.bed_syevd_lockstep_static(None, 1, 4, f(1e-5), 4, 1, L, V, None, None, None) == -1
+    assert lib.bed_syevd_lockstep_static(A, 1, 65, f(1e-5), 4, 1, L, V, None, None, None) == -3
+    assert lib.bed_syevd_lockstep_static(A, 1, 4, f(1e-5), -1, 1, L, V, None, None, None) == -7
+    assert lib.bed_syevd_lockstep_static(A, 1, 4, f(1e-5), 4, 2, L, V, None, None, None) == -7
+    assert lib.bed_syevd_lockstep_static(A, 0, 4, f(1e-5), 4, 1, L, V, None, None, None) == 0
+    assert lib.bed_syevd_lockstep_static(p(0x10000000), 4096, 64, f(1e-5), 64, 1, p(0x20000000), None, None, None,
+                                         None) == -8
+    assert lib.bed_syevd_lockstep_static_capacity() == 1 << 20
     f = ctypes.c_float
     assert lib.bed_spd_fn(None, 1, 4, 0, f(0.0), V, None, None, None) == -1        # NULL A
     assert lib.bed_spd_fn(A, 1, 4, 0, f(0.0), None, None, None, None) == -1        # NULL out
