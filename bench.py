@@ -12,7 +12,9 @@ inputs already resident in HBM.  The script prints ONE JSON line:
                dominant call, n = 32, is measured inside the timed region, the
                others in a second pass so that their events do not sit in it)
   roofline     the dominant kernel (n = 32): algorithmic flops / mean launch
-               duration against the fp32 vector peak
+               duration against the fp32 vector peak (datasheet, packed), the plain-FMA
+               peak, and ceilings measured in this run (plain-FMA kernel, device copy)
+  ceilings     those measured ceilings; environment: clocks, ROCm version, device
   cpu_baseline the float64 Jacobi oracle on the host cores, same inputs
 """
 from __future__ import annotations
@@ -28,7 +30,88 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_TFLOPS = 157.3   # 256 CU x 4 SIMD x 16 lanes x 2 (packed) x 2 flop x 2.4 GHz
+PEAK_FP32_PLAIN_FMA_TFLOPS = 78.6   # the same without packed instructions (v_fma_f32): what this build can reach
 PEAK_HBM_GBS = 8000.0
+
+
+def measure_ceilings(binding, torch, dev, stream):
+    """Rates this build reaches on this machine (HIP events on the launch stream, best of 5 launches):
+    plain-FMA throughput with the chip full, the FMA rate of 512 single-wavefront workgroups that
+    each run ONE dependent chain (the launch shape of the batch-512 calls), and a device copy."""
+    def best(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e-3)
+        return min(ts)
+
+    out = {}
+    blocks, threads, iters = 256 * 16, 256, 4096          # 16 wavefronts per SIMD
+    buf = torch.empty((blocks * threads,), dtype=torch.float32, device=dev)
+    fl = 2.0 * blocks * threads * 16 * iters
+    t = best(lambda: binding.bed_ceiling_fma(buf, blocks, threads, 16, iters))
+    out["plain_fma_tflops"] = fl / t / 1e12
+    out["plain_fma_command"] = f"bed_ceiling_fma(blocks={blocks}, threads={threads}, chains=16, iters={iters})"
+    blocks1, iters1 = 512, 1 << 16                          # one wavefront on every second SIMD, one chain each
+    buf1 = torch.empty((blocks1 * 64,), dtype=torch.float32, device=dev)
+    t1 = best(lambda: binding.bed_ceiling_fma(buf1, blocks1, 64, 1, iters1))
+    out["dependent_chain_512_waves_tflops"] = 2.0 * blocks1 * 64 * iters1 / t1 / 1e12
+    out["dependent_chain_ns_per_instruction"] = t1 / iters1 * 1e9
+    out["dependent_chain_command"] = f"bed_ceiling_fma(blocks={blocks1}, threads=64, chains=1, iters={iters1})"
+    nfl = (256 << 20) // 4                                  # 256 MiB each way
+    src = torch.empty((nfl,), dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    tc = best(lambda: binding.bed_ceiling_copy(src, dst, 256 * 32))
+    out["copy_gbs"] = 8.0 * nfl / tc / 1e9
+    out["copy_command"] = f"bed_ceiling_copy(count={nfl}, blocks={256 * 32})  # 256 MiB read + 256 MiB written"
+    del src, dst, buf, buf1
+    return out
+
+
+def environment(torch):
+    """Clocks, ROCm version and device as far as an ordinary user can read them."""
+    import subprocess
+    env = {"torch": torch.__version__, "hip": getattr(torch.version, "hip", None)}
+    try:
+        env["rocm_version"] = open("/opt/rocm/.info/version").read().strip()
+    except OSError:
+        env["rocm_version"] = None
+    pr = torch.cuda.get_device_properties(0)
+    env["device"] = pr.name
+    env["gcn_arch"] = getattr(pr, "gcnArchName", None)
+    env["compute_units"] = pr.multi_processor_count
+    env["max_engine_clock_mhz"] = getattr(pr, "clock_rate", 0) / 1000.0 or None
+    env["max_memory_clock_mhz"] = getattr(pr, "memory_clock_rate", 0) / 1000.0 or None
+    try:
+        r = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=20)
+        env["rocm_smi_clocks"] = json.loads(r.stdout) if r.returncode == 0 and r.stdout.strip() else None
+    except Exception:
+        env["rocm_smi_clocks"] = None
+    return env
+
+
+def traffic_from_profile():
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, but
+    only if that summary was taken from exactly the sources this library is built from (it
+    records their hash); otherwise None: a counter reading of another kernel is not this one's."""
+    import re
+    from paper_2207_04228_amd import build
+    tpath = os.path.join(ROOT, "profiles", "wave_kernel_n32_b512_counters.md")
+    if not os.path.exists(tpath):
+        return None, None
+    text = open(tpath).read()
+    m = re.search(r"^hbm_bytes_per_launch:\s*([0-9.]+)", text, flags=re.M)
+    h = re.search(r"^source_hash:\s*([0-9a-f]+)", text, flags=re.M)
+    if not m or not h or h.group(1) != build.source_hash():
+        return None, "profiles/wave_kernel_n32_b512_counters.md was taken from other sources than this build"
+    return float(m.group(1)), "profiles/wave_kernel_n32_b512_counters.md (same source hash as this build)"
 
 
 def flops_per_matrix(n: int, rotations: float, vectors: bool = True) -> float:
@@ -174,14 +257,18 @@ def main(argv=None) -> int:
         by = B * bytes_per_matrix(n)
         per_n[str(n)] = {
             "batch": B,
+            "kernel": binding.bed_kernel_variant(B, n),
             "kernel_us_mean": mean * 1e6,
             "kernel_us_median": float(np.median(durs)) * 1e6,
+            "kernel_us_p10": float(np.percentile(durs, 10)) * 1e6,
+            "kernel_us_p90": float(np.percentile(durs, 90)) * 1e6,
             "matrices_per_s": B / mean,
             "rotations_mean": rot_mean[n],
             "rotations_max": rot_max[n],
             "flops_per_launch": fl,
             "tflops": fl / mean / 1e12,
             "frac_fp32_valu": fl / mean / 1e12 / PEAK_FP32_TFLOPS,
+            "frac_plain_fma": fl / mean / 1e12 / PEAK_FP32_PLAIN_FMA_TFLOPS,
             "gbs": by / mean / 1e9,
             "frac_hbm": by / mean / 1e9 / PEAK_HBM_GBS,
         }
@@ -276,42 +363,57 @@ def main(argv=None) -> int:
                 extras["lockstep"][f"n{n}_{name}"] = {
                     "us": t * 1e6, "rows_dropped_mean": float(red.float().mean().item()),
                     "offdiag_left_max": float(off.max().item())}
-    for n, batch in (() if a.no_extras else ((4, 65536), (8, 65536), (16, 4096), (32, 4096), (64, 256), (128, 256))):
-        A32b = (workloads.config2(batch) if n == 4 else
-                workloads.config3(n, batch=batch) if n <= 32 else
-                workloads.config5(n, batch=batch) if n == 64 else workloads.covariance(batch, n, 4 * n, 1e-4, 1))
+    # Saturated batches.  n = 16 at batch 4096 is config 4 (Haar Q, lambda_i = i^-2); the sweeps of
+    # n = 4 and n = 8 go up to 2^20 matrices (config 2 / config 3 inputs, tiled beyond 65536) so that
+    # the rate with every SIMD holding several wavefronts is on record.
+    big = ((4, 4096), (4, 65536), (4, 1 << 18), (4, 1 << 20), (8, 4096), (8, 65536), (8, 1 << 18), (8, 1 << 20),
+           (16, 4096), (16, 65536), (32, 4096), (32, 16384), (64, 256), (128, 256))
+    for n, batch in (() if a.no_extras else big):
+        base = min(batch, 65536)
+        A32b = (workloads.config2(base) if n == 4 else
+                workloads.config4(batch=base) if n == 16 else
+                workloads.config3(n, batch=base) if n <= 32 else
+                workloads.config5(n, batch=base) if n == 64 else workloads.covariance(base, n, 4 * n, 1e-4, 1))
         Ab = torch.from_numpy(A32b).to(dev)
+        if batch > base:
+            Ab = Ab.repeat(batch // base, 1, 1).contiguous()
         evb = torch.empty((batch, n), dtype=torch.float32, device=dev)
         Vb = torch.empty((batch, n, n), dtype=torch.float32, device=dev)
         t = timed(lambda: binding.bed_syevd(Ab, evb, Vb), 10)
         _, _, _, rotb = binding.bed_syevd_info(Ab, evb, Vb)
         flb = batch * flops_per_matrix(n, float(rotb.float().mean().item()))
         extras["large_batch"][f"n{n}_b{batch}"] = {
+            "kernel": binding.bed_kernel_variant(batch, n),
             "kernel_us": t * 1e6, "matrices_per_s": batch / t,
             "gbs": batch * bytes_per_matrix(n) / t / 1e9,
+            "frac_hbm": batch * bytes_per_matrix(n) / t / 1e9 / PEAK_HBM_GBS,
             "tflops": flb / t / 1e12, "frac_fp32_valu": flb / t / 1e12 / PEAK_FP32_TFLOPS}
         del Ab, evb, Vb, A32b
 
     dom = per_n["32"]
-    # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary
-    # (FETCH_SIZE + WRITE_SIZE scaled by a plain copy of known size); null if it is absent.
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "wave_kernel_n32_b512_counters.md")
-    if os.path.exists(tpath):
-        import re
-        m = re.search(r"^hbm_bytes_per_launch:\s*([0-9.]+)", open(tpath).read(), flags=re.M)
-        if m:
-            traffic = float(m.group(1))
+    ceilings = measure_ceilings(binding, torch, dev, stream)
+    traffic, traffic_source = traffic_from_profile()
     roofline = {
-        "kernel": "bed::wave_kernel<32> (n=32, batch 512)",
+        "kernel": "bed::wave_kernel<32, true, 0> (n=32, batch 512)",
         "bound": "alu",
         "achieved": dom["tflops"],
         "peak": PEAK_FP32_TFLOPS,
         "unit": "TFLOP/s",
         "frac": dom["frac_fp32_valu"],
+        "peak_plain_fma": PEAK_FP32_PLAIN_FMA_TFLOPS,
+        "frac_vs_plain_fma": dom["tflops"] / PEAK_FP32_PLAIN_FMA_TFLOPS,
+        "peak_measured": ceilings["plain_fma_tflops"],
+        "frac_vs_measured": dom["tflops"] / ceilings["plain_fma_tflops"],
+        "launch_shape_ceiling": ceilings["dependent_chain_512_waves_tflops"],
+        "frac_vs_launch_shape_ceiling": dom["tflops"] / ceilings["dependent_chain_512_waves_tflops"],
         "traffic": traffic,
+        "traffic_source": traffic_source,
         "hbm_frac": dom["frac_hbm"],
+        "hbm_peak_measured_gbs": ceilings["copy_gbs"],
+        "hbm_frac_vs_measured": dom["gbs"] / ceilings["copy_gbs"],
         "launch_us": dom["kernel_us_mean"],
+        "launch_us_p10": dom["kernel_us_p10"],
+        "launch_us_p90": dom["kernel_us_p90"],
     }
 
     cpu_baseline = None
@@ -371,6 +473,8 @@ def main(argv=None) -> int:
         "per_n": per_n,
         "extras": None if a.no_extras else extras,
         "roofline": roofline,
+        "ceilings": ceilings,
+        "environment": environment(torch),
         "cpu_baseline": cpu_baseline,
         "parity": parity,
     }

@@ -264,6 +264,31 @@ size_t bed_syevd_lockstep_static_capacity(void);
 int bed_syevd_lockstep_static(const float* A, int batch, int n, float epsilon, int iterations, int uniform,
                               float* evals, float* evecs, float* offdiag, int* reductions, void* stream);
 
+/*
+ * Measurement aids (not part of the method): the rates this build reaches on this machine, reported by
+ * the benchmark beside the datasheet peaks.
+ *
+ * bed_ceiling_fma: every lane runs `chains` (1 or 16) independent chains of `iters` dependent
+ *   v_fma_f32 (plain, not packed); 2 * blocks * threads * chains * iters flops in total.
+ *   chains = 16 with several wavefronts per SIMD measures the vector ALU's plain-FMA throughput;
+ *   chains = 1 with one 64-thread block per SIMD measures what one dependent instruction stream
+ *   issues.  out: device, [blocks * threads] floats (written once at the end); threads a multiple
+ *   of 64, <= 1024; iters a multiple of 64.
+ * bed_ceiling_copy: plain device copy of `count` floats (count a multiple of 4, both pointers
+ *   16-byte aligned, buffers must not overlap) by `blocks` blocks of 256 threads; 8 * count bytes
+ *   of HBM traffic.
+ */
+int bed_ceiling_fma(float* out, int blocks, int threads, int chains, int iters, void* stream);
+int bed_ceiling_copy(const float* src, float* dst, size_t count, int blocks, void* stream);
+
+/*
+ * Name of the kernel that bed_syevd (want_vectors = 1) or its eigenvalues-only form
+ * (want_vectors = 0) launches for this batch and n, e.g. "wave_kernel<32>" (one wavefront per
+ * matrix, register arrays of 32), "lane_kernel<4>" (one matrix per lane), "block_kernel" (four
+ * wavefronts per matrix); static storage, NULL for arguments out of range.
+ */
+const char* bed_kernel_variant(int batch, int n, int want_vectors);
+
 /* Human-readable name of a bed_status value (static storage). */
 const char* bed_status_string(int status);
 

@@ -10,6 +10,9 @@ from .binding import (  # noqa: F401
     BED_GRAD_TAYLOR,
     BED_FN_SQRT,
     BedError,
+    bed_ceiling_copy,
+    bed_ceiling_fma,
+    bed_kernel_variant,
     bed_spd_fn,
     bed_spd_fn_backward,
     bed_syevd_backward,

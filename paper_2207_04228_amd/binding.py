@@ -64,12 +64,48 @@ def load_library():
         lib.bed_syevd_lockstep_static_capacity.restype = ctypes.c_size_t
         lib.bed_syevd_lockstep_static.argtypes = [vp, ci, ci, ctypes.c_float, ci, ci, vp, vp, vp, vp, vp]
         lib.bed_syevd_lockstep_static.restype = ci
+        lib.bed_ceiling_fma.argtypes = [vp, ci, ci, ci, ci, vp]
+        lib.bed_ceiling_fma.restype = ci
+        lib.bed_ceiling_copy.argtypes = [vp, vp, ctypes.c_size_t, ci, vp]
+        lib.bed_ceiling_copy.restype = ci
+        lib.bed_kernel_variant.argtypes = [ci, ci, ci]
+        lib.bed_kernel_variant.restype = ctypes.c_char_p
         lib.bed_status_string.argtypes = [ci]
         lib.bed_status_string.restype = ctypes.c_char_p
         lib.bed_version.argtypes = []
         lib.bed_version.restype = ci
         _lib = lib
     return _lib
+
+
+def bed_kernel_variant(batch: int, n: int, want_vectors: bool = True) -> str:
+    """Name of the kernel bed_syevd launches for this batch and n."""
+    r = load_library().bed_kernel_variant(int(batch), int(n), 1 if want_vectors else 0)
+    if r is None:
+        raise ValueError("batch or n out of range")
+    return r.decode()
+
+
+def bed_ceiling_fma(out, blocks, threads, chains, iters, *, stream=None):
+    """Measurement aid: `chains` independent chains of `iters` plain FMAs per lane.
+    Returns the flops of the launch."""
+    import torch
+    _check_dev(out, "out", torch.float32, (int(blocks) * int(threads),))
+    st = load_library().bed_ceiling_fma(_ptr(out), int(blocks), int(threads), int(chains), int(iters), _stream(stream))
+    if st != 0:
+        raise BedError(st, "bed_ceiling_fma")
+    return 2.0 * blocks * threads * chains * iters
+
+
+def bed_ceiling_copy(src, dst, blocks, *, stream=None):
+    """Measurement aid: plain device copy src -> dst.  Returns the bytes moved (read + write)."""
+    import torch
+    _check_dev(src, "src", torch.float32)
+    _check_dev(dst, "dst", torch.float32, tuple(src.shape), src)
+    st = load_library().bed_ceiling_copy(_ptr(src), _ptr(dst), src.numel(), int(blocks), _stream(stream))
+    if st != 0:
+        raise BedError(st, "bed_ceiling_copy")
+    return 8.0 * src.numel()
 
 
 def bed_version() -> int:

@@ -38,6 +38,19 @@ def _newer(target: str, deps) -> bool:
     return all(os.path.getmtime(d) <= t for d in deps)
 
 
+def source_hash() -> str:
+    """sha256 over the device and host sources of libbed.so (csrc/ and include/bed.h): identifies
+    the kernels a stored profile was taken from."""
+    import hashlib
+    h = hashlib.sha256()
+    files = sorted(glob.glob(os.path.join(CSRC, "*.hip")) + glob.glob(os.path.join(CSRC, "*.h"))
+                   + glob.glob(os.path.join(CSRC, "*.hpp")) + glob.glob(os.path.join(ROOT, "include", "*.h")))
+    for f in files:
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
 def build(force: bool = False, remarks: bool = False, jobs: int = 8) -> str:
     os.makedirs(OBJ, exist_ok=True)
     sources = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
@@ -87,7 +100,11 @@ def main(argv=None):
     ap.add_argument("--force", action="store_true")
     ap.add_argument("--remarks", action="store_true", help="write per-kernel resource usage to _build/*.log")
     ap.add_argument("-j", "--jobs", type=int, default=8)
+    ap.add_argument("--source-hash", action="store_true", help="print the hash of the sources and exit")
     a = ap.parse_args(argv)
+    if a.source_hash:
+        print(source_hash())
+        return 0
     print(build(a.force, a.remarks, a.jobs))
 
 

@@ -283,6 +283,12 @@ int bed_syevd_lockstep_static(const float* A, int batch, int n, float epsilon, i
                             true, stream);
 }
 
+const char* bed_kernel_variant(int batch, int n, int want_vectors) {
+    (void)want_vectors;   // the eigenvalues-only form runs the same kernel family with the V part compiled out
+    if (batch < 0 || n < 1 || n > BED_MAX_N) return nullptr;
+    return bed::kernel_variant(batch, n);
+}
+
 const char* bed_status_string(int status) {
     switch (status) {
         case BED_OK: return "BED_OK";

@@ -84,6 +84,9 @@ hipError_t launch_lockstep(const LockstepArgs& args, hipStream_t stream);
 constexpr size_t kLockstepScratchBytes = 1u << 20;
 hipError_t lockstep_scratch(void** ptr);
 
+// Name of the kernel that serves a full decomposition of this batch and n.
+const char* kernel_variant(int batch, int n);
+
 // Enqueue one launch; returns the status of that launch.
 hipError_t launch(const KernelArgs& args, int stage, bool want_v, hipStream_t stream);
 

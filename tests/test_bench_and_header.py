@@ -24,6 +24,25 @@ def test_work_model_matches_its_definition():
         assert abs(bench.flops_per_matrix(n, R, vectors=False) - ((4.0 / 3.0) * n ** 3 + 20 * R)) < 1e-6
     assert abs(bench.flops_per_matrix(32, 32 * 32) - 304e3) < 2e3        # the nominal 304 k flops of a 32 x 32 matrix
     assert bench.PEAK_FP32_TFLOPS == 157.3 and bench.PEAK_HBM_GBS == 8000.0
+    assert bench.PEAK_FP32_PLAIN_FMA_TFLOPS == 78.6      # v_fma_f32 only: what a build without packed fp32 can reach
+
+
+def test_traffic_is_reported_only_for_the_profiled_sources(tmp_path, monkeypatch):
+    """roofline.traffic comes from the committed counter summary only while that summary's
+    source hash equals the hash of the sources the library is built from."""
+    sys.path.insert(0, ROOT)
+    import bench
+    from paper_2207_04228_amd import build
+    prof = tmp_path / "profiles"
+    prof.mkdir()
+    f = prof / "wave_kernel_n32_b512_counters.md"
+    monkeypatch.setattr(bench, "ROOT", str(tmp_path))
+    f.write_text(f"source_hash: {build.source_hash()}\nhbm_bytes_per_launch: 4879718\n")
+    assert bench.traffic_from_profile()[0] == 4879718.0
+    f.write_text("source_hash: 0123456789abcdef\nhbm_bytes_per_launch: 4879718\n")
+    assert bench.traffic_from_profile()[0] is None
+    f.write_text("hbm_bytes_per_launch: 4879718\n")
+    assert bench.traffic_from_profile()[0] is None
 
 
 def test_public_header_is_plain_c(tmp_path):

@@ -68,6 +68,18 @@ def test_argument_validation_is_host_side(lib):
     assert lib.bed_syevd_lockstep_static(p(0x10000000), 4096, 64, f(1e-5), 64, 1, p(0x20000000), None, None, None,
                                          None) == -8
     assert lib.bed_syevd_lockstep_static_capacity() == 1 << 20
+    # measurement aids
+    assert lib.bed_ceiling_fma(None, 1, 64, 1, 64, None) == -1
+    assert lib.bed_ceiling_fma(A, 1, 65, 1, 64, None) == -7
+    assert lib.bed_ceiling_fma(A, 1, 64, 2, 64, None) == -7
+    assert lib.bed_ceiling_fma(A, 1, 64, 1, 100, None) == -7
+    assert lib.bed_ceiling_copy(A, None, 4, 1, None) == -1
+    assert lib.bed_ceiling_copy(p(0x10004), L, 4, 1, None) == -4
+    assert lib.bed_ceiling_copy(A, L, 6, 1, None) == -7
+    assert binding.bed_kernel_variant(512, 32) == "wave_kernel<32>"
+    assert binding.bed_kernel_variant(65536, 4) == "lane_kernel<4>"
+    assert binding.bed_kernel_variant(256, 100) == "block_kernel"
+    assert lib.bed_kernel_variant(1, 129, 1) is None
     f = ctypes.c_float
     assert lib.bed_spd_fn(None, 1, 4, 0, f(0.0), V, None, None, None) == -1        # NULL A
     assert lib.bed_spd_fn(A, 1, 4, 0, f(0.0), None, None, None, None) == -1        # NULL out
