@@ -98,6 +98,28 @@ int bed_syevd_info(const float* A, int batch, int n, float* evals, float* evecs,
                    int* info, unsigned* rotations, void* stream);
 
 /*
+ * bed_syevd_info through ONE kernel family, whatever the batch size (for parity tests of every
+ * family at every batch size, and for measuring the batch sizes at which the automatic choice
+ * should change).  Same method, arguments and outputs; the families differ in how matrices
+ * map onto the machine:
+ *   BED_FAMILY_AUTO    what bed_syevd does: chosen from n and batch (see bed_kernel_variant)
+ *   BED_FAMILY_WAVE    one wavefront per matrix, n <= 64
+ *   BED_FAMILY_PACKED  four matrices per wavefront (one row of 16 lanes each), n <= 16
+ *   BED_FAMILY_LANE    one matrix per lane, n <= 8
+ *   BED_FAMILY_BLOCK   four wavefronts per matrix, 64 < n <= 128
+ * BED_ERR_N if the family does not serve this n, BED_ERR_ARG for an unknown family.
+ */
+typedef enum {
+    BED_FAMILY_AUTO = 0,
+    BED_FAMILY_WAVE = 1,
+    BED_FAMILY_PACKED = 2,
+    BED_FAMILY_LANE = 3,
+    BED_FAMILY_BLOCK = 4
+} bed_family;
+int bed_syevd_family(const float* A, int batch, int n, float* evals, float* evecs, int* info,
+                     unsigned* rotations, int family, void* stream);
+
+/*
  * Stage hook 1 -- Householder tridiagonalisation only (Sec. 3.1, Eqs. (2)-(7)):
  * A_b = P_b T_b P_b^T with T symmetric tridiagonal.
  *   d  device, [batch][n]   diagonal of T

@@ -5,6 +5,11 @@ The library is loaded lazily on first use; importing this package never
 touches the GPU.
 """
 from .binding import (  # noqa: F401
+    BED_FAMILY_AUTO,
+    BED_FAMILY_BLOCK,
+    BED_FAMILY_LANE,
+    BED_FAMILY_PACKED,
+    BED_FAMILY_WAVE,
     BED_FN_INV_SQRT,
     BED_GRAD_EXACT,
     BED_GRAD_TAYLOR,

@@ -44,6 +44,8 @@ def load_library():
         lib.bed_syevd.restype = ci
         lib.bed_syevd_info.argtypes = [vp, ci, ci, vp, vp, vp, vp, vp]
         lib.bed_syevd_info.restype = ci
+        lib.bed_syevd_family.argtypes = [vp, ci, ci, vp, vp, vp, vp, ci, vp]
+        lib.bed_syevd_family.restype = ci
         lib.bed_tridiag.argtypes = [vp, ci, ci, vp, vp, vp, vp]
         lib.bed_tridiag.restype = ci
         lib.bed_tridiag_qr.argtypes = [vp, vp, ci, ci, vp, vp, vp, vp, vp]
@@ -175,8 +177,12 @@ def bed_syevd(A, evals=None, evecs=None, *, want_vectors=True, stream=None):
     return evals, evecs
 
 
-def bed_syevd_info(A, evals=None, evecs=None, *, want_vectors=True, stream=None):
-    """bed_syevd plus (info int32 [batch], rotations int32-view of uint32 [batch])."""
+BED_FAMILY_AUTO, BED_FAMILY_WAVE, BED_FAMILY_PACKED, BED_FAMILY_LANE, BED_FAMILY_BLOCK = range(5)
+
+
+def bed_syevd_info(A, evals=None, evecs=None, *, want_vectors=True, stream=None, family=BED_FAMILY_AUTO):
+    """bed_syevd plus (info int32 [batch], rotations int32-view of uint32 [batch]); `family`
+    forces one kernel family (bed_syevd_family)."""
     import torch
     _check_dev(A, "A", torch.float32)
     batch, n = _square_batch(A)
@@ -191,8 +197,8 @@ def bed_syevd_info(A, evals=None, evecs=None, *, want_vectors=True, stream=None)
         _check_dev(evecs, "evecs", torch.float32, (batch, n, n), A)
     info = torch.empty((batch,), dtype=torch.int32, device=A.device)
     rot = torch.empty((batch,), dtype=torch.int32, device=A.device)
-    st = load_library().bed_syevd_info(_ptr(A), batch, n, _ptr(evals), _ptr(evecs),
-                                       _ptr(info), _ptr(rot), _stream(stream))
+    st = load_library().bed_syevd_family(_ptr(A), batch, n, _ptr(evals), _ptr(evecs),
+                                         _ptr(info), _ptr(rot), int(family), _stream(stream))
     if st != 0:
         raise BedError(st, "bed_syevd_info")
     return evals, evecs, info, rot

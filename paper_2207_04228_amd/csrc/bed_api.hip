@@ -21,9 +21,9 @@ int check_common(int batch, int n) {
     return BED_OK;
 }
 
-int run(const bed::KernelArgs& args, int stage, bool want_v, void* stream) {
+int run(const bed::KernelArgs& args, int stage, bool want_v, void* stream, int family = bed::kFamilyAuto) {
     if (args.batch == 0) return BED_OK;
-    hipError_t err = bed::launch(args, stage, want_v, static_cast<hipStream_t>(stream));
+    hipError_t err = bed::launch(args, stage, want_v, static_cast<hipStream_t>(stream), family);
     return err == hipSuccess ? BED_OK : BED_ERR_LAUNCH;
 }
 
@@ -84,8 +84,15 @@ extern "C" {
 
 int bed_syevd_info(const float* A, int batch, int n, float* evals, float* evecs, int* info,
                    unsigned* rotations, void* stream) {
+    return bed_syevd_family(A, batch, n, evals, evecs, info, rotations, BED_FAMILY_AUTO, stream);
+}
+
+int bed_syevd_family(const float* A, int batch, int n, float* evals, float* evecs, int* info,
+                     unsigned* rotations, int family, void* stream) {
     int st = check_common(batch, n);
     if (st != BED_OK) return st;
+    if (family < BED_FAMILY_AUTO || family > BED_FAMILY_BLOCK) return BED_ERR_ARG;
+    if (!bed::family_serves(family, n)) return BED_ERR_N;
     if (batch == 0) return BED_OK;
     if (!A || !evals) return BED_ERR_NULL;
     if (misaligned(A) || misaligned(evals) || misaligned(evecs) || misaligned(info) || misaligned(rotations))
@@ -101,7 +108,7 @@ int bed_syevd_info(const float* A, int batch, int n, float* evals, float* evecs,
     args.rotations = rotations;
     args.batch = batch;
     args.n = n;
-    return run(args, bed::kFull, evecs != nullptr, stream);
+    return run(args, bed::kFull, evecs != nullptr, stream, family);
 }
 
 int bed_syevd(const float* A, int batch, int n, float* evals, float* evecs, void* stream) {

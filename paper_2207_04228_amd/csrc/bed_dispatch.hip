@@ -4,6 +4,7 @@
 namespace bed {
 
 hipError_t launch_lane(const KernelArgs&, bool, hipStream_t);
+hipError_t launch_packed(const KernelArgs&, bool, hipStream_t);
 hipError_t launch_wave_n4(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n8(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n12(const KernelArgs&, int, bool, hipStream_t);
@@ -20,20 +21,47 @@ hipError_t launch_block(const KernelArgs&, int, bool, hipStream_t);
 
 namespace {
 
-enum Family { kLaneFamily, kWaveFamily, kBlockFamily };
+constexpr int kPackedFromBatch = 2560;
+constexpr int kLane4FromBatch = 20480;
+constexpr int kLane8FromBatch = 32768;
+
+enum Family { kLaneFamily, kPackedFamily, kWaveFamily, kBlockFamily };
 struct Choice {
     Family family;
     int N;               // register-array size of the instantiation (0 for the block kernel)
     const char* name;
 };
 
-// The one place that decides which kernel serves a problem.
-Choice choose(int batch, int n, int stage) {
-    // Tiny matrices in very large batches: one matrix per lane (64 per wavefront).  Below these
-    // batch sizes the chip is not full and the one-wavefront-per-matrix kernels, whose
-    // per-matrix latency is much lower, finish first (measured crossovers on MI355X).
-    if (stage == kFull && n <= 4 && batch >= 6144) return {kLaneFamily, 4, "lane_kernel<4>"};
-    if (stage == kFull && n <= 8 && batch >= 12288) return {kLaneFamily, 8, "lane_kernel<8>"};
+Choice wave_choice(int n);
+
+// The one place that decides which kernel serves a problem.  `forced` (kFamilyAuto unless a test
+// or a measurement asks for one family) must be able to serve n: the caller has checked.
+Choice choose(int batch, int n, int stage, int forced) {
+    if (forced == kFamilyLane) return n <= 4 ? Choice{kLaneFamily, 4, "lane_kernel<4>"} : Choice{kLaneFamily, 8, "lane_kernel<8>"};
+    if (forced == kFamilyPacked) {
+        if (n <= 4) return {kPackedFamily, 4, "packed_kernel<4>"};
+        if (n <= 8) return {kPackedFamily, 8, "packed_kernel<8>"};
+        if (n <= 12) return {kPackedFamily, 12, "packed_kernel<12>"};
+        return {kPackedFamily, 16, "packed_kernel<16>"};
+    }
+    if (forced == kFamilyWave) return wave_choice(n);
+    if (forced == kFamilyBlock) return {kBlockFamily, 0, "block_kernel"};
+    // Measured crossovers on MI355X (us per launch, eigenvectors on; wave / packed / lane):
+    //   n = 4:  batch 2048: 8.4 / 8.6 / 13.0   4096: 11.5 / 9.1 / 13.7   16384: 27.7 / 13.2 / 14.2   32768: 49 / 21.7 / 14.9
+    //   n = 8:  batch 2048: 17.2 / 17.8 / 49.5  4096: 25.3 / 18.0 / 49.4  32768: 127 / 58.1 / 56.6    65536: 231 / 96.9 / 57.6
+    //   n = 16: batch 2048: 34.1 / 36.3         3072: 42.6 / 35.4         4096: 51.6 / 35.5           16384: 152 / 76.7
+    // Below kPackedFromBatch the chip is not full and one wavefront per matrix, whose per-matrix
+    // latency is lowest, finishes first.  Then four matrices per wavefront (n <= 16) share the
+    // instructions of the scalar recurrence.  For tiny matrices in very large batches one matrix per
+    // lane (64 per wavefront) has no redundant work at all, but a latency several times higher.
+    if (stage == kFull && n <= 4 && batch >= kLane4FromBatch) return {kLaneFamily, 4, "lane_kernel<4>"};
+    if (stage == kFull && n <= 8 && batch >= kLane8FromBatch) return {kLaneFamily, 8, "lane_kernel<8>"};
+    if (stage == kFull && n <= 16 && batch >= kPackedFromBatch) return choose(batch, n, stage, kFamilyPacked);
+    if (n <= 64) return wave_choice(n);
+    return {kBlockFamily, 0, "block_kernel"};     // 64 < n <= 128: four wavefronts per matrix
+}
+
+Choice wave_choice(int n) {
     if (n <= 4) return {kWaveFamily, 4, "wave_kernel<4>"};
     if (n <= 8) return {kWaveFamily, 8, "wave_kernel<8>"};
     if (n <= 12) return {kWaveFamily, 12, "wave_kernel<12>"};
@@ -45,18 +73,29 @@ Choice choose(int batch, int n, int stage) {
     if (n <= 40) return {kWaveFamily, 40, "wave_kernel<40>"};
     if (n <= 48) return {kWaveFamily, 48, "wave_kernel<48>"};
     if (n <= 56) return {kWaveFamily, 56, "wave_kernel<56>"};
-    if (n <= 64) return {kWaveFamily, 64, "wave_kernel<64>"};
-    return {kBlockFamily, 0, "block_kernel"};     // 64 < n <= 128: four wavefronts per matrix
+    return {kWaveFamily, 64, "wave_kernel<64>"};
 }
 
 }  // namespace
 
-const char* kernel_variant(int batch, int n) { return choose(batch, n, kFull).name; }
+const char* kernel_variant(int batch, int n) { return choose(batch, n, kFull, kFamilyAuto).name; }
 
-hipError_t launch(const KernelArgs& args, int stage, bool want_v, hipStream_t stream) {
+bool family_serves(int family, int n) {
+    switch (family) {
+        case kFamilyAuto: return n >= 1 && n <= 128;
+        case kFamilyWave: return n >= 1 && n <= 64;
+        case kFamilyPacked: return n >= 1 && n <= 16;
+        case kFamilyLane: return n >= 1 && n <= 8;
+        case kFamilyBlock: return n > 64 && n <= 128;
+        default: return false;
+    }
+}
+
+hipError_t launch(const KernelArgs& args, int stage, bool want_v, hipStream_t stream, int forced) {
     if (args.batch == 0) return hipSuccess;
-    const Choice c = choose(args.batch, args.n, stage);
+    const Choice c = choose(args.batch, args.n, stage, forced);
     if (c.family == kLaneFamily) return launch_lane(args, want_v, stream);
+    if (c.family == kPackedFamily) return launch_packed(args, want_v, stream);
     if (c.family == kBlockFamily) return launch_block(args, stage, want_v, stream);
     switch (c.N) {
         case 4: return launch_wave_n4(args, stage, want_v, stream);

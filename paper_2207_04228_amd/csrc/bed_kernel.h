@@ -87,8 +87,13 @@ hipError_t lockstep_scratch(void** ptr);
 // Name of the kernel that serves a full decomposition of this batch and n.
 const char* kernel_variant(int batch, int n);
 
-// Enqueue one launch; returns the status of that launch.
-hipError_t launch(const KernelArgs& args, int stage, bool want_v, hipStream_t stream);
+// Kernel families (values of bed_family in bed.h).
+enum FamilyId { kFamilyAuto = 0, kFamilyWave = 1, kFamilyPacked = 2, kFamilyLane = 3, kFamilyBlock = 4 };
+bool family_serves(int family, int n);
+
+// Enqueue one launch; returns the status of that launch.  `forced`: a family other than
+// kFamilyAuto (full decomposition only; the caller has checked family_serves).
+hipError_t launch(const KernelArgs& args, int stage, bool want_v, hipStream_t stream, int forced = kFamilyAuto);
 
 }  // namespace bed
 

@@ -1,0 +1,11 @@
+// Instantiation of the four-matrices-per-wavefront kernels (n <= 16).
+#include "bed_packed_kernel.hpp"
+
+namespace bed {
+hipError_t launch_packed(const KernelArgs& args, bool want_v, hipStream_t stream) {
+    if (args.n <= 4) return launch_packed_n<4>(args, want_v, stream);
+    if (args.n <= 8) return launch_packed_n<8>(args, want_v, stream);
+    if (args.n <= 12) return launch_packed_n<12>(args, want_v, stream);
+    return launch_packed_n<16>(args, want_v, stream);
+}
+}  // namespace bed

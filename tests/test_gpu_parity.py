@@ -18,14 +18,19 @@ ORTH_TOL = 1e-5
 ANGLE_TOL = 1e-3
 
 
-def _solve_gpu(A32, want_vectors=True, info=False):
+LANE = 3     # BED_FAMILY_LANE: one matrix per lane, whatever the batch size
+
+
+def _solve_gpu(A32, want_vectors=True, info=False, family=0):
     import torch
     from paper_2207_04228_amd import binding
     dev = torch.device("cuda:0")
     At = torch.from_numpy(A32).to(dev)
-    if info:
-        ev, V, inf, rot = binding.bed_syevd_info(At, want_vectors=want_vectors)
+    if info or family:
+        ev, V, inf, rot = binding.bed_syevd_info(At, want_vectors=want_vectors, family=family)
         torch.cuda.synchronize()
+        if not info:
+            return ev.cpu().numpy(), None if V is None else V.cpu().numpy()
         return (ev.cpu().numpy(), None if V is None else V.cpu().numpy(),
                 inf.cpu().numpy(), rot.cpu().numpy())
     ev, V = binding.bed_syevd(At, want_vectors=want_vectors)
@@ -34,12 +39,12 @@ def _solve_gpu(A32, want_vectors=True, info=False):
     return ev.cpu().numpy(), None if V is None else V.cpu().numpy()
 
 
-def _check(A32, name):
+def _check(A32, name, family=0):
     from oracle import jacobi
     from oracle.acceptance import evaluate
     print(f"[parity] {name} shape={A32.shape}", flush=True)
     lam_o, V_o = jacobi.syevd(A32)
-    lam_g, V_g = _solve_gpu(A32)
+    lam_g, V_g = _solve_gpu(A32, family=family)
     assert np.isfinite(lam_g).all() and np.isfinite(V_g).all()
     assert np.all(np.diff(lam_g, axis=1) >= 0), "eigenvalues not ascending"
     acc = evaluate(A32, lam_g, V_g, lam_o, V_o)
@@ -167,14 +172,14 @@ def test_eigenvalues_only_matches_full_path():
         assert np.array_equal(lam_full, lam_only)
 
 
-def _check_eigenvalues_only(A32, name):
+def _check_eigenvalues_only(A32, name, family=0):
     """evecs = NULL (the economic eigenvalue calculation of Sec. 3.2.4) against the ORACLE:
     ascending, finite, within 1e-5 ||A||_2 of the Jacobi eigenvalues, info = 0, and the
     trace / Frobenius identities of the spectrum."""
     from oracle import jacobi
     print(f"[parity] {name} eigenvalues only, shape={A32.shape}", flush=True)
     lam_o, _ = jacobi.syevd(A32)
-    lam_g, V, info, rot = _solve_gpu(A32, want_vectors=False, info=True)
+    lam_g, V, info, rot = _solve_gpu(A32, want_vectors=False, info=True, family=family)
     assert V is None
     assert np.isfinite(lam_g).all()
     assert np.all(np.diff(lam_g, axis=1) >= 0), "eigenvalues not ascending"
@@ -213,8 +218,8 @@ def test_eigenvalues_only_against_oracle_block_kernel():
 @pytest.mark.parametrize("n,batch", [(4, 6144), (4, 6144 + 64 + 21), (3, 7001), (8, 12288), (8, 12288 + 128 + 5),
                                      (6, 13003)])
 def test_eigenvalues_only_against_oracle_lane_kernel(n, batch):
-    """evecs = NULL at the batch sizes that dispatch to the one-matrix-per-lane kernels
-    (n <= 4 from batch 6144, n <= 8 from batch 12288), full and ragged last wavefronts."""
+    """evecs = NULL through the one-matrix-per-lane kernels (lane_kernel<4, false>,
+    lane_kernel<8, false>), full and ragged last wavefronts; once forced, once as dispatched."""
     from paper_2207_04228_amd import workloads
     if n == 4:
         A = workloads.config2(65536)[:batch]
@@ -224,7 +229,18 @@ def test_eigenvalues_only_against_oracle_lane_kernel(n, batch):
         rng = np.random.default_rng(4200 + n)
         A = rng.standard_normal((batch, n, n))
         A = (0.5 * (A + A.transpose(0, 2, 1))).astype(np.float32)
-    _check_eigenvalues_only(np.ascontiguousarray(A), f"lane_n{n}_b{batch}")
+    _check_eigenvalues_only(np.ascontiguousarray(A), f"lane_n{n}_b{batch}", family=LANE)
+    _check_eigenvalues_only(np.ascontiguousarray(A), f"auto_n{n}_b{batch}")
+
+
+def test_eigenvalues_only_against_oracle_where_the_lane_kernels_are_dispatched():
+    from paper_2207_04228_amd import binding, workloads
+    A = workloads.config2(65536)[:20480 + 64 + 9]
+    assert binding.bed_kernel_variant(A.shape[0], 4) == "lane_kernel<4>"
+    _check_eigenvalues_only(np.ascontiguousarray(A), "dispatched_lane_n4")
+    A = workloads.config3(8, batch=32768 + 7)
+    assert binding.bed_kernel_variant(A.shape[0], 8) == "lane_kernel<8>"
+    _check_eigenvalues_only(A, "dispatched_lane_n8")
 
 
 def test_no_fallback_deflation_on_the_five_configs():
@@ -334,7 +350,8 @@ def test_lane_kernels_ragged_batches(n, batch):
     rng = np.random.default_rng(7000 + 10 * n)
     A = rng.standard_normal((batch, n, n))
     A = (0.5 * (A + A.transpose(0, 2, 1))).astype(np.float32)
-    _check(A, f"lane_n{n}_b{batch}")
+    _check(A, f"lane_n{n}_b{batch}", family=LANE)
+    _check(A, f"auto_n{n}_b{batch}")
 
 
 def test_lane_kernel_agrees_with_wave_kernel():
@@ -343,8 +360,8 @@ def test_lane_kernel_agrees_with_wave_kernel():
     from oracle.acceptance import evaluate
     from paper_2207_04228_amd import workloads
     A = workloads.config2(65536)[:8192]
-    lam_lane, V_lane = _solve_gpu(A)            # batch 8192: lane kernel
-    lam_wave, V_wave = _solve_gpu(A[:4096])     # batch 4096: wave kernel
+    lam_lane, V_lane = _solve_gpu(A, family=LANE)
+    lam_wave, V_wave = _solve_gpu(A[:4096], family=1)
     acc = evaluate(A[:4096], lam_lane[:4096], V_lane[:4096], lam_wave.astype(np.float64), V_wave.astype(np.float64))
     w = acc.worst()
     assert w["eval_err"] <= 2e-6 and w["angle"] <= 1e-3, w
@@ -360,7 +377,7 @@ def test_lane_kernel_degenerate_and_nan():
     A[6] = 0.0
     A[7] = np.eye(4, dtype=np.float32)
     A[70, 2, 1] = np.nan
-    ev, V, info, rot = binding.bed_syevd_info(torch.from_numpy(A).to("cuda:0"))
+    ev, V, info, rot = binding.bed_syevd_info(torch.from_numpy(A).to("cuda:0"), family=LANE)
     torch.cuda.synchronize()
     ev, V, info = ev.cpu().numpy(), V.cpu().numpy(), info.cpu().numpy()
     assert np.array_equal(ev[5], np.array([-1.0, 2.0, 2.0, 3.0], dtype=np.float32))

@@ -52,7 +52,7 @@ def test_lane_kernel_with_repeated_eigenvalues():
         batch = 12288 + 17
         lam = np.round(rng.uniform(0, 2, (batch, n))) + 1.0
         A = workloads.from_spectrum(lam, seed=n)
-        ev, V, info, rot = binding.bed_syevd_info(torch.from_numpy(A).to("cuda:0"))
+        ev, V, info, rot = binding.bed_syevd_info(torch.from_numpy(A).to("cuda:0"), family=binding.BED_FAMILY_LANE)
         torch.cuda.synchronize()
         assert int((info & 0xFFFF).max()) == 0 and int(rot.max()) <= 6 * n * n
         print(f"[repeated] lane kernel n={n}: fallback deflations: {int((info >> 16).sum())}",

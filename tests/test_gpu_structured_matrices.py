@@ -32,17 +32,17 @@ def test_structured_matrices(n):
           f"fallback deflations: {relaxed}", flush=True)
 
 
-@pytest.mark.parametrize("batch", [2, 8192])
-def test_fixed_point_of_the_double_shift(batch):
+@pytest.mark.parametrize("batch,family", [(2, 0), (8192, 1), (8192, 2), (8192, 3)])
+def test_fixed_point_of_the_double_shift(batch, family):
     """diag(1, 0, 1) with unit off-diagonals is mapped onto itself (up to signs) by a pair of
     sweeps shifted with the two eigenvalues of its trailing block, in exact arithmetic for
-    ever; the solver has to leave it after a few iterations, in the wave kernel (small batch)
-    and in the one-matrix-per-lane kernel (large batch)."""
+    ever; the solver has to leave it after a few iterations, in every kernel family that serves
+    n = 3 (one wavefront per matrix, four matrices per wavefront, one matrix per lane)."""
     import torch
     from paper_2207_04228_amd import binding, workloads
     W = workloads.wilkinson_tridiagonal(3).astype(np.float32)
     A = np.stack([W * np.float32(s) for s in (1.0, -1.0, 0.125, 3.0)] * (batch // 4 + 1))[:batch]
-    ev, V, info, rot = binding.bed_syevd_info(torch.from_numpy(np.ascontiguousarray(A)).to("cuda:0"))
+    ev, V, info, rot = binding.bed_syevd_info(torch.from_numpy(np.ascontiguousarray(A)).to("cuda:0"), family=family)
     torch.cuda.synchronize()
     assert int(info.max()) == 0
     assert int(rot.max()) <= 44, int(rot.max())

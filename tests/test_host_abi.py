@@ -28,7 +28,7 @@ def _declared_symbols():
 
 def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
-    assert {"bed_syevd", "bed_syevd_info", "bed_tridiag", "bed_tridiag_qr", "bed_tridiag_qr_sweeps", "bed_spd_fn", "bed_syevd_backward", "bed_spd_fn_backward", "bed_syevd_lockstep", "bed_syevd_lockstep_workspace",
+    assert {"bed_syevd", "bed_syevd_info", "bed_syevd_family", "bed_tridiag", "bed_tridiag_qr", "bed_tridiag_qr_sweeps", "bed_spd_fn", "bed_syevd_backward", "bed_spd_fn_backward", "bed_syevd_lockstep", "bed_syevd_lockstep_workspace",
             "bed_status_string", "bed_version"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
@@ -78,6 +78,10 @@ def test_argument_validation_is_host_side(lib):
     assert lib.bed_ceiling_copy(A, L, 6, 1, None) == -7
     assert binding.bed_kernel_variant(512, 32) == "wave_kernel<32>"
     assert binding.bed_kernel_variant(65536, 4) == "lane_kernel<4>"
+    assert binding.bed_kernel_variant(4096, 16) == "packed_kernel<16>"
+    assert binding.bed_kernel_variant(4096, 4) == "packed_kernel<4>"
+    assert binding.bed_kernel_variant(2048, 16) == "wave_kernel<16>"
+    assert binding.bed_kernel_variant(4096, 17) == "wave_kernel<20>"
     assert binding.bed_kernel_variant(256, 100) == "block_kernel"
     assert lib.bed_kernel_variant(1, 129, 1) is None
     f = ctypes.c_float
