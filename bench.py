@@ -380,11 +380,15 @@ def main(argv=None) -> int:
         evb = torch.empty((batch, n), dtype=torch.float32, device=dev)
         Vb = torch.empty((batch, n, n), dtype=torch.float32, device=dev)
         t = timed(lambda: binding.bed_syevd(Ab, evb, Vb), 10)
+        t_ev = timed(lambda: binding.bed_syevd(Ab, evb, None, want_vectors=False), 10)
+        t_fn = timed(lambda: binding.bed_spd_fn(Ab, binding.BED_FN_INV_SQRT, 1e-6, out=Vb), 10)
         _, _, _, rotb = binding.bed_syevd_info(Ab, evb, Vb)
         flb = batch * flops_per_matrix(n, float(rotb.float().mean().item()))
         extras["large_batch"][f"n{n}_b{batch}"] = {
             "kernel": binding.bed_kernel_variant(batch, n),
             "kernel_us": t * 1e6, "matrices_per_s": batch / t,
+            "eigenvalues_only_us": t_ev * 1e6,
+            "spd_inv_sqrt_us": t_fn * 1e6,
             "gbs": batch * bytes_per_matrix(n) / t / 1e9,
             "frac_hbm": batch * bytes_per_matrix(n) / t / 1e9 / PEAK_HBM_GBS,
             "tflops": flb / t / 1e12, "frac_fp32_valu": flb / t / 1e12 / PEAK_FP32_TFLOPS}

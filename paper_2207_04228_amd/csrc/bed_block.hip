@@ -250,7 +250,8 @@ __global__ __launch_bounds__(BT) void block_kernel(KernelArgs args) {
     int info = 0;
     float d_lane[2];
     float2* const sP = sP_all + wv * BPA;
-    qr_iterations<BN, true, WANT_V, BLD>(sP, sV, lane, 32 * wv + (lane & 31), n, rotations, info, d_lane, args, b);
+    PhaseClock clk;
+    qr_iterations<BN, true, WANT_V, BLD>(sP, sV, lane, 32 * wv + (lane & 31), n, rotations, info, d_lane, args, b, clk);
     __syncthreads();       // all four wavefronts leave after the same iteration; V is complete
 
     if (STAGE == kSpectral) {

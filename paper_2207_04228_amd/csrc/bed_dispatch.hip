@@ -3,8 +3,8 @@
 
 namespace bed {
 
-hipError_t launch_lane(const KernelArgs&, bool, hipStream_t);
-hipError_t launch_packed(const KernelArgs&, bool, hipStream_t);
+hipError_t launch_lane(const KernelArgs&, int, bool, hipStream_t);
+hipError_t launch_packed(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n4(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n8(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n12(const KernelArgs&, int, bool, hipStream_t);
@@ -54,9 +54,12 @@ Choice choose(int batch, int n, int stage, int forced) {
     // latency is lowest, finishes first.  Then four matrices per wavefront (n <= 16) share the
     // instructions of the scalar recurrence.  For tiny matrices in very large batches one matrix per
     // lane (64 per wavefront) has no redundant work at all, but a latency several times higher.
-    if (stage == kFull && n <= 4 && batch >= kLane4FromBatch) return {kLaneFamily, 4, "lane_kernel<4>"};
-    if (stage == kFull && n <= 8 && batch >= kLane8FromBatch) return {kLaneFamily, 8, "lane_kernel<8>"};
-    if (stage == kFull && n <= 16 && batch >= kPackedFromBatch) return choose(batch, n, stage, kFamilyPacked);
+    // The fused spectral function follows the same choice; the stage hooks stay with one wavefront
+    // per matrix.
+    const bool whole = (stage == kFull || stage == kSpectral);
+    if (whole && n <= 4 && batch >= kLane4FromBatch) return {kLaneFamily, 4, "lane_kernel<4>"};
+    if (whole && n <= 8 && batch >= kLane8FromBatch) return {kLaneFamily, 8, "lane_kernel<8>"};
+    if (whole && n <= 16 && batch >= kPackedFromBatch) return choose(batch, n, stage, kFamilyPacked);
     if (n <= 64) return wave_choice(n);
     return {kBlockFamily, 0, "block_kernel"};     // 64 < n <= 128: four wavefronts per matrix
 }
@@ -94,8 +97,8 @@ bool family_serves(int family, int n) {
 hipError_t launch(const KernelArgs& args, int stage, bool want_v, hipStream_t stream, int forced) {
     if (args.batch == 0) return hipSuccess;
     const Choice c = choose(args.batch, args.n, stage, forced);
-    if (c.family == kLaneFamily) return launch_lane(args, want_v, stream);
-    if (c.family == kPackedFamily) return launch_packed(args, want_v, stream);
+    if (c.family == kLaneFamily) return launch_lane(args, stage, want_v, stream);
+    if (c.family == kPackedFamily) return launch_packed(args, stage, want_v, stream);
     if (c.family == kBlockFamily) return launch_block(args, stage, want_v, stream);
     switch (c.N) {
         case 4: return launch_wave_n4(args, stage, want_v, stream);

@@ -37,6 +37,7 @@ struct KernelArgs {
     uint32_t sweep_cap;  // at most this many sweeps (0: the default cap of 30 n); kQrPartial stops there
     int* info;           // [batch] or nullptr
     uint32_t* rotations; // [batch] or nullptr
+    unsigned long long* phases;  // [batch][8] cycle counts per phase; read only by the profiling build
     int batch;
     int n;
 };

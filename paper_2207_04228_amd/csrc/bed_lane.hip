@@ -2,8 +2,8 @@
 #include "bed_lane_kernel.hpp"
 
 namespace bed {
-hipError_t launch_lane(const KernelArgs& args, bool want_v, hipStream_t stream) {
-    if (args.n <= 4) return launch_lane_n<4>(args, want_v, stream);
-    return launch_lane_n<8>(args, want_v, stream);
+hipError_t launch_lane(const KernelArgs& args, int stage, bool want_v, hipStream_t stream) {
+    if (args.n <= 4) return launch_lane_n<4>(args, stage, want_v, stream);
+    return launch_lane_n<8>(args, stage, want_v, stream);
 }
 }  // namespace bed

@@ -47,7 +47,9 @@ __device__ __forceinline__ uint32_t sort_key(float x) {
 
 }  // namespace lanek
 
-template <int N, bool WANT_V>
+// STAGE: kFull, or kSpectral (the fused V f(max(Lambda, floor)) V^T of Sec. 4.2-4.4 / App.
+// B.1-B.3: formed in registers from V and lambda, eigenvectors never written).
+template <int N, bool WANT_V, int STAGE>
 __global__ __launch_bounds__(64) void lane_kernel(KernelArgs args) {
     using namespace lanek;
     constexpr int NN = N * N;
@@ -304,7 +306,7 @@ __global__ __launch_bounds__(64) void lane_kernel(KernelArgs args) {
         }
         rank[k] = rk;
     }
-    // eigenvalues through the staging buffer (stride n+... reuse MS)
+    // eigenvalues through the staging buffer
     __syncthreads();
     if (mine) {
 #pragma unroll
@@ -312,7 +314,7 @@ __global__ __launch_bounds__(64) void lane_kernel(KernelArgs args) {
             if (k < n) stage[lane * MS + rank[k]] = lam[k] * inv_scale;
     }
     __syncthreads();
-    {
+    if (args.evals) {
         float* __restrict__ Eb = args.evals + b0 * n;
         const float rcp = 1.0f / (float)n;
         for (int idx = lane; idx < nb * n; idx += 64) {
@@ -320,7 +322,41 @@ __global__ __launch_bounds__(64) void lane_kernel(KernelArgs args) {
             Eb[idx] = stage[m * MS + (idx - m * n)];
         }
     }
-    if (WANT_V) {
+    if (STAGE == kSpectral) {
+        // F = V f(Lambda) V^T in registers, row by row: t[k] = V[i][k] f(lambda_k), then
+        // F[i][j] = sum_k t[k] V[j][k] for j <= i, mirrored into the staging buffer
+        float fl[N];
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+            const float x = fmaxf(lam[k] * inv_scale, args.fn_floor);
+            fl[k] = (k < n) ? ((args.fn == kFnInvSqrt) ? __builtin_amdgcn_rsqf(x) : __builtin_amdgcn_sqrtf(x)) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            float t[N];
+#pragma unroll
+            for (int k = 0; k < N; ++k) t[k] = v[i][k] * fl[k];
+#pragma unroll
+            for (int j = 0; j <= i; ++j) {
+                float acc = 0.f;
+#pragma unroll
+                for (int k = 0; k < N; ++k) acc = fmaf(t[k], v[j][k], acc);
+                if (mine && i < n && j < n) {
+                    stage[lane * MS + i * n + j] = acc;
+                    stage[lane * MS + j * n + i] = acc;
+                }
+            }
+        }
+        __syncthreads();
+        float* __restrict__ Fb = args.fn_out + b0 * nn;
+        const float rcp = 1.0f / (float)nn;
+        for (int idx = lane; idx < nb * nn; idx += 64) {
+            const int m = (int)(((float)idx + 0.5f) * rcp);
+            Fb[idx] = stage[m * MS + (idx - m * nn)];
+        }
+    }
+    if (WANT_V && STAGE == kFull) {
         __syncthreads();
         if (mine) {
 #pragma unroll
@@ -345,10 +381,11 @@ __global__ __launch_bounds__(64) void lane_kernel(KernelArgs args) {
 }
 
 template <int N>
-static hipError_t launch_lane_n(const KernelArgs& args, bool want_v, hipStream_t stream) {
+static hipError_t launch_lane_n(const KernelArgs& args, int stage, bool want_v, hipStream_t stream) {
     const unsigned blocks = (unsigned)((args.batch + 63) / 64);
-    if (want_v) return enqueue(lane_kernel<N, true>, dim3(blocks), dim3(64), stream, args);
-    return enqueue(lane_kernel<N, false>, dim3(blocks), dim3(64), stream, args);
+    if (stage == kSpectral) return enqueue(lane_kernel<N, true, kSpectral>, dim3(blocks), dim3(64), stream, args);
+    if (want_v) return enqueue(lane_kernel<N, true, kFull>, dim3(blocks), dim3(64), stream, args);
+    return enqueue(lane_kernel<N, false, kFull>, dim3(blocks), dim3(64), stream, args);
 }
 
 }  // namespace bed

@@ -2,10 +2,10 @@
 #include "bed_packed_kernel.hpp"
 
 namespace bed {
-hipError_t launch_packed(const KernelArgs& args, bool want_v, hipStream_t stream) {
-    if (args.n <= 4) return launch_packed_n<4>(args, want_v, stream);
-    if (args.n <= 8) return launch_packed_n<8>(args, want_v, stream);
-    if (args.n <= 12) return launch_packed_n<12>(args, want_v, stream);
-    return launch_packed_n<16>(args, want_v, stream);
+hipError_t launch_packed(const KernelArgs& args, int stage, bool want_v, hipStream_t stream) {
+    if (args.n <= 4) return launch_packed_n<4>(args, stage, want_v, stream);
+    if (args.n <= 8) return launch_packed_n<8>(args, stage, want_v, stream);
+    if (args.n <= 12) return launch_packed_n<12>(args, stage, want_v, stream);
+    return launch_packed_n<16>(args, stage, want_v, stream);
 }
 }  // namespace bed

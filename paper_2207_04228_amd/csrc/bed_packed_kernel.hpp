@@ -133,8 +133,9 @@ __device__ __forceinline__ void chain_rotate(Chain& S, float ek, float dk1, floa
 }  // namespace packed
 
 // N: register-array size (4, 8, 12, 16), n <= N at run time.  One workgroup = one wavefront =
-// up to four consecutive matrices of the batch.
-template <int N, bool WANT_V>
+// up to four consecutive matrices of the batch.  STAGE: kFull, or kSpectral (the fused
+// V f(max(Lambda, floor)) V^T of Sec. 4.2-4.4 / App. B.1-B.3, eigenvectors never written).
+template <int N, bool WANT_V, int STAGE>
 __global__ __launch_bounds__(64) void packed_kernel(KernelArgs args) {
     using namespace packed;
     static_assert(N <= RW, "a matrix must fit one row of lanes");
@@ -410,6 +411,26 @@ __global__ __launch_bounds__(64) void packed_kernel(KernelArgs args) {
         info = max(info, (int)__builtin_popcount(bad));
         info |= (int)(min(relaxed, 0x7FFFu) << 16);
     }
+    if (STAGE == kSpectral) {
+        // F = V f(Lambda) V^T straight from V and lambda in LDS: lane r forms w[k] = V[r][k] f(lambda_k)
+        // once, then F[r][c] = sum_k w[k] V[c][k] for every c; F is symmetric, so the entry is stored
+        // at F[c][r] and the lanes of a row write consecutive addresses.
+        float w[N];
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+            float lam = sP[k].y * inv_scale;
+            lam = fmaxf(lam, args.fn_floor);
+            const float fl = (args.fn == kFnInvSqrt) ? __builtin_amdgcn_rsqf(lam) : __builtin_amdgcn_sqrtf(lam);
+            w[k] = (k < n) ? sV[k * LD + r] * fl : 0.f;
+        }
+        float* __restrict__ Fb = args.fn_out + (m0 + grp) * nn;
+        for (int c = 0; c < n; ++c) {
+            float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int k = 0; k < N; ++k) acc[k & 3] = fmaf(w[k], sV[k * LD + c], acc[k & 3]);
+            if (mine && r < n) Fb[c * n + r] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+        }
+    }
     const uint32_t mykey = sort_key(dl);
     int rank = 0;
     for (int j = 0; j < n; ++j) {
@@ -423,7 +444,7 @@ __global__ __launch_bounds__(64) void packed_kernel(KernelArgs args) {
         sI[rank] = r;                      // output column `rank` comes from column r of V
     }
     wave_sync();
-    {
+    if (args.evals) {
         float* __restrict__ Eb = args.evals + m0 * n;
         const float rcp_n = 1.0f / (float)n;
         for (int idx = lane; idx < cnt * n; idx += 64) {
@@ -431,7 +452,7 @@ __global__ __launch_bounds__(64) void packed_kernel(KernelArgs args) {
             Eb[idx] = sE_all[m * RW + (idx - m * n)];
         }
     }
-    if (WANT_V) {
+    if (WANT_V && STAGE == kFull) {
         float* __restrict__ Vb = args.evecs + m0 * nn;
         const float rcp_nn = 1.0f / (float)nn, rcp_n = 1.0f / (float)n;
         for (int idx = lane; idx < cnt * nn; idx += 64) {
@@ -449,10 +470,11 @@ __global__ __launch_bounds__(64) void packed_kernel(KernelArgs args) {
 }
 
 template <int N>
-static hipError_t launch_packed_n(const KernelArgs& args, bool want_v, hipStream_t stream) {
+static hipError_t launch_packed_n(const KernelArgs& args, int stage, bool want_v, hipStream_t stream) {
     const unsigned blocks = (unsigned)((args.batch + packed::PER_WAVE - 1) / packed::PER_WAVE);
-    if (want_v) return enqueue(packed_kernel<N, true>, dim3(blocks), dim3(64), stream, args);
-    return enqueue(packed_kernel<N, false>, dim3(blocks), dim3(64), stream, args);
+    if (stage == kSpectral) return enqueue(packed_kernel<N, true, kSpectral>, dim3(blocks), dim3(64), stream, args);
+    if (want_v) return enqueue(packed_kernel<N, true, kFull>, dim3(blocks), dim3(64), stream, args);
+    return enqueue(packed_kernel<N, false, kFull>, dim3(blocks), dim3(64), stream, args);
 }
 
 }  // namespace bed

@@ -22,6 +22,36 @@
 
 namespace bed {
 
+// Cycle counts per phase of one wavefront's work, for the phase-resolved profile
+// (paper_2207_04228_amd/phase_profile.py builds a separate library with BED_PHASE_CLOCKS defined).
+// In the product build every member is an empty inline function and the object holds nothing.
+enum Phase { kPhLoad = 0, kPhTridiag, kPhBoundary, kPhFill, kPhSteady, kPhDrain, kPhStore, kPhIterations, kPhCount };
+struct PhaseClock {
+#ifdef BED_PHASE_CLOCKS
+    unsigned long long last;
+    unsigned long long acc[kPhCount];
+    __device__ __forceinline__ void start() {
+        for (int i = 0; i < kPhCount; ++i) acc[i] = 0;
+        last = __builtin_readcyclecounter();
+    }
+    __device__ __forceinline__ void lap(int phase) {
+        const unsigned long long t = __builtin_readcyclecounter();
+        acc[phase] += t - last;
+        last = t;
+    }
+    __device__ __forceinline__ void count(int phase) { acc[phase] += 1; }
+    __device__ __forceinline__ void write(unsigned long long* out, int b, int lane) const {
+        if (out && lane == 0)
+            for (int i = 0; i < kPhCount; ++i) out[(size_t)b * kPhCount + i] = acc[i];
+    }
+#else
+    __device__ __forceinline__ void start() {}
+    __device__ __forceinline__ void lap(int) {}
+    __device__ __forceinline__ void count(int) {}
+    __device__ __forceinline__ void write(unsigned long long*, int, int) const {}
+#endif
+};
+
 namespace {
 
 // Relative deflation tolerance: |e_k| <= kEps (|d_k| + |d_k+1|), kEps = 4 * 2^-23.  Inside a
@@ -213,7 +243,8 @@ __device__ __forceinline__ void chain_finish(const Chain& S, float& e_out, float
 template <int N, bool HALF, bool WANT_V, int LD>
 __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV, const int lane, const int vrow,
                                               const int n, uint32_t& rotations, int& info,
-                                              float (&d_lane)[(N + 63) / 64], const KernelArgs& args, const int b) {
+                                              float (&d_lane)[(N + 63) / 64], const KernelArgs& args, const int b,
+                                              PhaseClock& clk) {
     const bool roleB = lane >= 32;
     const uint32_t cap = args.sweep_cap ? args.sweep_cap : 30u * (uint32_t)n;
     uint32_t sweeps = 0;
@@ -271,6 +302,7 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
         }
         stall = same ? stall + 1 : 0;
         if (any == 0 || sweeps >= cap) break;
+        clk.count(kPhIterations);
         // active window [lo, hi]: e[hi-1] is the last live entry, e[lo-1] the last dead one below it
         int hi, lo;
         if (NB == 2 && nz[NB - 1] != 0) {
@@ -326,6 +358,7 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
             // from registers.  At step t: B handles row t-2 with A's outputs of step t-1,
             // while A handles row t.
             float pE, pD, pV = 0.f;     // A's outputs of the previous step
+            clk.lap(kPhBoundary);
             // t = lo: A rotates row lo
             chain_rotate<WANT_V>(A, q0.x, q0.y, y0, pE, pD, pV);
             BED_REFILL(q0, y0, lo);
@@ -386,6 +419,7 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
                     prevD = oD;                                                 \
                     prevV = oV;                                                 \
                 } while (0)
+                clk.lap(kPhFill);
                 int t = lo + 2;
                 for (; t + 1 < hi; t += 2) {
                     BED_STEPH(q0, y0, 0);
@@ -399,6 +433,7 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
                     xP += 1;
                 }
 #undef BED_STEPH
+                clk.lap(kPhSteady);
                 // The three closing steps belong to B alone; the A lanes' stores would now land
                 // beyond the window, so they are parked in the padding behind the arrays.
                 xV = roleB ? xV : (sV + (N + 3) * LD + vrow);
@@ -469,6 +504,7 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
                     prevE = oE;                                                 \
                     prevD = oD;                                                 \
                 } while (0)
+                clk.lap(kPhFill);
                 int t = lo + 2;
                 for (; t + 1 < hi; t += 2) {
                     BED_STEPW(q0, y0, 0);
@@ -482,6 +518,7 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
                     xP += 1;
                 }
 #undef BED_STEPW
+                clk.lap(kPhSteady);
                 // closing steps: B alone; the A lanes' T stores are parked in the padding
                 xP = roleB ? xP : (sP + (N + 3));
                 float fE, fD, fx;
@@ -513,7 +550,9 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
         }
 #undef BED_REFILL
         wave_sync();
+        clk.lap(kPhDrain);
     }
+    clk.lap(kPhBoundary);      // the last deflation test, which found nothing left
     info = 0;
 #pragma unroll
     for (int bk = 0; bk < NB; ++bk) {
@@ -562,6 +601,8 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
     const int n = args.n;
 
     float inv_scale = 1.f;
+    PhaseClock clk;
+    clk.start();
 
     constexpr bool GIVEN_T = (STAGE == kQrOnly || STAGE == kQrPartial);
     if (!GIVEN_T && HALF && WANT_V) {
@@ -597,6 +638,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         const float myscale = roleP ? 1.f : scale;
 #pragma unroll
         for (int c = 0; c < N; ++c) x[c] *= myscale;
+        clk.lap(kPhLoad);
 #pragma unroll
         for (int J = 0; J < N; ++J) {
             const float dJ = read_lane(x[J], J);      // final once columns 0..J-1 are reduced
@@ -671,6 +713,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         pow2_scale(wave_max_nonneg<W>(amax), scale, inv_scale);
 #pragma unroll
         for (int c = 0; c < N; ++c) a[c] *= scale;
+        clk.lap(kPhLoad);
 
         // ---- Householder tridiagonalisation, column J reduced at step J ----
         // Branch-free: a step that has nothing to do (J >= n-2, or the column is
@@ -778,6 +821,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
 
     uint32_t rotations = 0;
     int info = 0;
+    clk.lap(kPhTridiag);
 
     if (STAGE == kTridiagOnly) {
         if (lane < n) {
@@ -796,7 +840,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
     } else {
         // ---- shifted QR iterations on the tridiagonal in sP ----
         float d_lane[1];
-        qr_iterations<N, HALF, WANT_V, LD>(sP, sV, lane, row, n, rotations, info, d_lane, args, b);
+        qr_iterations<N, HALF, WANT_V, LD>(sP, sV, lane, row, n, rotations, info, d_lane, args, b, clk);
         const float dl = d_lane[0];
         const int vrow = row;
         if (STAGE == kQrPartial) {
@@ -882,6 +926,8 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         if (args.info) args.info[b] = info;
         if (args.rotations) args.rotations[b] = rotations;
     }
+    clk.lap(kPhStore);
+    clk.write(args.phases, b, lane);
 }
 
 // ---------------------------------------------------------------------------

@@ -145,3 +145,37 @@ def test_without_eigenvalue_output_and_batch_edges():
 def test_large_batch_small_n():
     from paper_2207_04228_amd import workloads
     _check(workloads.config2(20000), 1, 1e-6, "config2 batch 20000 (n=4)")
+
+
+@pytest.mark.parametrize("fn", [0, 1])
+def test_where_the_packed_and_lane_kernels_are_dispatched(fn):
+    """The fused spectral function at the batch sizes that go to four matrices per wavefront
+    (n <= 16 from batch 2560) and to one matrix per lane (n <= 4 from batch 20480, n <= 8 from batch
+    32768), ragged last wavefronts included; 65536 matrices of 4 x 4 are the shape of App. B.3."""
+    from paper_2207_04228_amd import binding, workloads
+    cases = [("packed_kernel<16>", workloads.config4()),
+             ("packed_kernel<12>", workloads.covariance(2560 + 3, 12, 48, 1e-4, 61)),
+             ("packed_kernel<8>", workloads.config3(8, batch=4096 + 1)),
+             ("packed_kernel<4>", workloads.config2(4096)),
+             ("lane_kernel<4>", workloads.config2(65536)),
+             ("lane_kernel<4>", workloads.covariance(20480 + 64 + 13, 3, 16, 1e-3, 62)),
+             ("lane_kernel<8>", workloads.config3(8, batch=32768 + 7)),
+             ("lane_kernel<8>", workloads.covariance(32768 + 64, 6, 24, 1e-4, 63))]
+    for variant, A in cases:
+        assert binding.bed_kernel_variant(A.shape[0], A.shape[-1]) == variant
+        _check(A, fn, 1e-6, f"{variant} batch {A.shape[0]} n={A.shape[-1]}")
+
+
+def test_floor_and_degenerate_rows_in_the_packed_and_lane_kernels():
+    """Zero, diagonal and indefinite matrices inside large batches: the floor acts per matrix."""
+    from paper_2207_04228_amd import workloads
+    for batch, n in ((4096, 8), (32768, 8), (20480, 4)):
+        A = workloads.covariance(batch, n, 4 * n, 1e-4, 64 + n).copy()
+        A[5] = 0.0
+        A[6] = np.diag(np.linspace(0.5, 4.0, n)).astype(np.float32)
+        A[7] = -A[7]
+        F, ev, info = _gpu(A, 1, 0.25)
+        assert (info == 0).all()
+        assert np.allclose(F[5], 2.0 * np.eye(n), atol=1e-6) and (ev[5] == 0).all()
+        assert np.allclose(F[6], np.diag(1.0 / np.sqrt(np.maximum(np.linspace(0.5, 4.0, n), 0.25))), atol=1e-6)
+        assert np.allclose(F[7], 2.0 * np.eye(n), atol=1e-5)        # every eigenvalue negative: all floored
