@@ -138,6 +138,11 @@ def main(argv=None) -> int:
     ap.add_argument("--workload", default="headline", choices=["headline"])
     ap.add_argument("--only-n", type=int, default=0,
                     help="profiling aid: launch only the batch-512 call of this n, --steps times, and exit")
+    ap.add_argument("--only-batch", type=int, default=512,
+                    help="with --only-n: the batch size (512: the headline input of that n; 4096 with n = 16: config 4; "
+                         "otherwise config 2 / config 3 inputs, tiled beyond 65536)")
+    ap.add_argument("--ceilings-only", action="store_true",
+                    help="profiling aid: run only the measured-ceiling kernels (plain FMA, dependent chain, copy) and exit")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="profiling aid: run a plain device-to-device copy of MIB mebibytes --steps times and exit "
                          "(reference reading for the FETCH_SIZE / WRITE_SIZE counters)")
@@ -169,18 +174,30 @@ def main(argv=None) -> int:
         print(json.dumps({"copy_calibration_bytes": nbytes, "launches": a.steps}))
         return 0
 
+    if a.ceilings_only:
+        print(json.dumps(measure_ceilings(binding, torch, dev, torch.cuda.current_stream())))
+        return 0
+
     points = workloads.headline_points()          # [(n, A32)], batch 512 each
     if a.only_n:
-        points = [pt for pt in points if pt[0] == a.only_n]
-        n, A32 = points[0]
+        n = a.only_n
+        if a.only_batch == 512:
+            A32 = dict(points)[n]
+        else:
+            base = min(a.only_batch, 65536)
+            A32 = (workloads.config2(base) if n == 4 else workloads.config4(batch=base) if n == 16 else
+                   workloads.config3(n, batch=base))
         A = torch.from_numpy(A32).to(dev)
+        if a.only_batch > A.shape[0]:
+            A = A.repeat(a.only_batch // A.shape[0], 1, 1).contiguous()
         ev = torch.empty((A.shape[0], n), dtype=torch.float32, device=dev)
         V = torch.empty((A.shape[0], n, n), dtype=torch.float32, device=dev)
         torch.cuda.synchronize()
         for _ in range(a.steps):
             binding.bed_syevd(A, ev, V)
         torch.cuda.synchronize()
-        print(json.dumps({"only_n": n, "launches": a.steps, "batch": int(A.shape[0])}))
+        print(json.dumps({"only_n": n, "launches": a.steps, "batch": int(A.shape[0]),
+                          "kernel": binding.bed_kernel_variant(int(A.shape[0]), n)}))
         return 0
     bufs = []
     for n, A32 in points:
