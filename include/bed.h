@@ -104,7 +104,8 @@ int bed_syevd_info(const float* A, int batch, int n, float* evals, float* evecs,
  * map onto the machine:
  *   BED_FAMILY_AUTO    what bed_syevd does: chosen from n and batch (see bed_kernel_variant)
  *   BED_FAMILY_WAVE    one wavefront per matrix, n <= 64
- *   BED_FAMILY_PACKED  four matrices per wavefront (one row of 16 lanes each), n <= 16
+ *   BED_FAMILY_PACKED  four matrices per wavefront (16 lanes each) for n <= 16, two (32 lanes each)
+ *                      for 16 < n <= 32
  *   BED_FAMILY_LANE    one matrix per lane, n <= 8
  *   BED_FAMILY_BLOCK   four wavefronts per matrix, 64 < n <= 128
  * BED_ERR_N if the family does not serve this n, BED_ERR_ARG for an unknown family.

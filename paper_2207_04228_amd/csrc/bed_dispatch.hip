@@ -22,6 +22,7 @@ hipError_t launch_block(const KernelArgs&, int, bool, hipStream_t);
 namespace {
 
 constexpr int kPackedFromBatch = 2560;
+constexpr int kPacked32FromBatch = 4096;
 constexpr int kLane4FromBatch = 20480;
 constexpr int kLane8FromBatch = 32768;
 
@@ -42,7 +43,9 @@ Choice choose(int batch, int n, int stage, int forced) {
         if (n <= 4) return {kPackedFamily, 4, "packed_kernel<4>"};
         if (n <= 8) return {kPackedFamily, 8, "packed_kernel<8>"};
         if (n <= 12) return {kPackedFamily, 12, "packed_kernel<12>"};
-        return {kPackedFamily, 16, "packed_kernel<16>"};
+        if (n <= 16) return {kPackedFamily, 16, "packed_kernel<16>"};
+        if (n <= 24) return {kPackedFamily, 24, "packed_kernel<24>"};
+        return {kPackedFamily, 32, "packed_kernel<32>"};
     }
     if (forced == kFamilyWave) return wave_choice(n);
     if (forced == kFamilyBlock) return {kBlockFamily, 0, "block_kernel"};
@@ -50,6 +53,8 @@ Choice choose(int batch, int n, int stage, int forced) {
     //   n = 4:  batch 2048: 8.4 / 8.6 / 13.0   4096: 11.5 / 9.1 / 13.7   16384: 27.7 / 13.2 / 14.2   32768: 49 / 21.7 / 14.9
     //   n = 8:  batch 2048: 17.2 / 17.8 / 49.5  4096: 25.3 / 18.0 / 49.4  32768: 127 / 58.1 / 56.6    65536: 231 / 96.9 / 57.6
     //   n = 16: batch 2048: 34.1 / 36.3         3072: 42.6 / 35.4         4096: 51.6 / 35.5           16384: 152 / 76.7
+    //   n = 24: batch 2048: 73.4 / 80.4         3072: 93.7 / 97.0         4096: 112 / 100             16384: 356 / 289
+    //   n = 32: batch 2048: 115 / 123           3072: 145 / 161           4096: 179 / 163             16384: 571 / 496
     // Below kPackedFromBatch the chip is not full and one wavefront per matrix, whose per-matrix
     // latency is lowest, finishes first.  Then four matrices per wavefront (n <= 16) share the
     // instructions of the scalar recurrence.  For tiny matrices in very large batches one matrix per
@@ -60,6 +65,9 @@ Choice choose(int batch, int n, int stage, int forced) {
     if (whole && n <= 4 && batch >= kLane4FromBatch) return {kLaneFamily, 4, "lane_kernel<4>"};
     if (whole && n <= 8 && batch >= kLane8FromBatch) return {kLaneFamily, 8, "lane_kernel<8>"};
     if (whole && n <= 16 && batch >= kPackedFromBatch) return choose(batch, n, stage, kFamilyPacked);
+    // two matrices per wavefront for 16 < n <= 32: a smaller gain (the one-wavefront kernel already
+    // serves both sweeps of such a matrix with one instruction stream), from a larger batch
+    if (whole && n <= 32 && batch >= kPacked32FromBatch) return choose(batch, n, stage, kFamilyPacked);
     if (n <= 64) return wave_choice(n);
     return {kBlockFamily, 0, "block_kernel"};     // 64 < n <= 128: four wavefronts per matrix
 }
@@ -87,7 +95,7 @@ bool family_serves(int family, int n) {
     switch (family) {
         case kFamilyAuto: return n >= 1 && n <= 128;
         case kFamilyWave: return n >= 1 && n <= 64;
-        case kFamilyPacked: return n >= 1 && n <= 16;
+        case kFamilyPacked: return n >= 1 && n <= 32;
         case kFamilyLane: return n >= 1 && n <= 8;
         case kFamilyBlock: return n > 64 && n <= 128;
         default: return false;

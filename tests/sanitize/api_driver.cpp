@@ -69,7 +69,7 @@ int main() {
     EXPECT(bed_syevd_info(A, 8, 16, L, V, dev<int>(0x60000001), R, nullptr), BED_ERR_ALIGN);
 
     EXPECT(bed_syevd_family(A, 8, 16, L, V, I, R, BED_FAMILY_PACKED, nullptr), BED_OK);
-    EXPECT(bed_syevd_family(A, 8, 17, L, V, I, R, BED_FAMILY_PACKED, nullptr), BED_ERR_N);
+    EXPECT(bed_syevd_family(A, 8, 33, L, V, I, R, BED_FAMILY_PACKED, nullptr), BED_ERR_N);
     EXPECT(bed_syevd_family(A, 8, 9, L, V, I, R, BED_FAMILY_LANE, nullptr), BED_ERR_N);
     EXPECT(bed_syevd_family(A, 8, 16, L, V, I, R, 5, nullptr), BED_ERR_ARG);
     EXPECT(bed_syevd_family(A, 8, 16, L, V, I, R, -1, nullptr), BED_ERR_ARG);

@@ -44,10 +44,10 @@ LANE = 3
 WAVE = 1
 
 
-@pytest.mark.parametrize("n", list(range(1, 17)))
+@pytest.mark.parametrize("n", list(range(1, 33)))
 def test_packed_kernel_every_n(n):
-    """Four matrices per wavefront, every n it serves; batches that leave 1, 2, 3 rows of the last
-    wavefront empty; indefinite input."""
+    """Four (n <= 16) or two (n <= 32) matrices per wavefront, every n it serves; batches that
+    leave groups of the last wavefront empty; indefinite input."""
     rng = np.random.default_rng(8100 + n)
     for batch in (1, 2, 3, 4, 37, 258):
         A = rng.standard_normal((batch, n, n))
@@ -62,6 +62,9 @@ def test_packed_kernel_on_the_configs():
     _check(workloads.config3(8), PACKED, "packed_config3_n8")
     _check(workloads.config3(16), PACKED, "packed_config3_n16")
     _check(workloads.config4(), PACKED, "packed_config4")
+    _check(workloads.config3(24), PACKED, "packed_config3_n24")
+    _check(workloads.config3(32), PACKED, "packed_config3_n32")
+    _check(workloads.config3(32, batch=4099), PACKED, "packed_n32_b4099")
 
 
 def test_packed_kernel_mixed_convergence_in_one_wavefront():
@@ -96,7 +99,7 @@ def test_packed_kernel_nan_is_confined_to_its_row():
 
 def test_packed_kernel_structured_and_repeated():
     from paper_2207_04228_amd import workloads
-    for n in (5, 8, 13, 16):
+    for n in (5, 8, 13, 16, 21, 32):
         for name, A in workloads.structured_cases(n, 16, seed=900 + n):
             _check(A, PACKED, f"packed_structured_n{n}_{name}", allow_fallback=True)
         rng = np.random.default_rng(8300 + n)
@@ -123,7 +126,7 @@ def test_wave_kernel_at_large_batches(n, batch):
 def test_family_argument_checks():
     import torch
     from paper_2207_04228_amd import binding
-    A = torch.zeros((4, 32, 32), dtype=torch.float32, device="cuda:0")
+    A = torch.zeros((4, 33, 33), dtype=torch.float32, device="cuda:0")
     for fam in (PACKED, LANE, 4):
         with pytest.raises(binding.BedError) as e:
             binding.bed_syevd_info(A, family=fam)
