@@ -2,11 +2,14 @@
  * bed -- batched symmetric eigendecomposition for AMD MI355X (gfx950).
  *
  * C ABI of libbed.so.  Every pointer marked "device" is GPU memory owned by
- * the caller; the library allocates nothing and keeps no state between calls.
- * All entry points are asynchronous: they enqueue one kernel on `stream`
- * (a hipStream_t passed as void*; NULL = the default stream) and return.
- * Argument errors are detected on the host, return a negative bed_status and
- * enqueue nothing.  Entry points are re-entrant and thread-safe.
+ * the caller; the library allocates nothing and keeps no state between calls
+ * (one exception, stated there: bed_syevd_lockstep_static works in scratch
+ * memory built into the library, which calls on the same GPU share).
+ * All entry points are asynchronous: they enqueue their kernels (one, except
+ * for the lock-step procedure) on `stream` (a hipStream_t passed as void*;
+ * NULL = the default stream) and return.  Argument errors are detected on the
+ * host, return a negative bed_status and enqueue nothing.  Entry points are
+ * re-entrant and thread-safe (same exception).
  *
  * Method (arXiv 2207.04228, Sec. 3): Householder tridiagonalisation
  * A = P T P^T (Sec. 3.1), then QR iterations on T by Givens rotations with
