@@ -20,6 +20,30 @@ inline hipError_t enqueue(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipSt
     return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, argv, 0, stream);
 }
 
+// Lane-strided copy of `count` consecutive elements between global memory and an on-chip layout
+// (every instruction touches 64 consecutive addresses).  CHUNK elements per lane are in flight at
+// once: all loads of a chunk (global loads, or the LDS reads that feed global stores) are issued
+// before the first value is consumed, instead of one memory round trip per element.
+template <int CHUNK, typename Load, typename Store>
+__device__ __forceinline__ void chunked_copy(int count, int lane, Load&& load, Store&& store) {
+    for (int base = lane; base < count; base += 64 * CHUNK) {
+        float t[CHUNK];
+#pragma unroll
+        for (int k = 0; k < CHUNK; ++k) {
+            const int idx = base + 64 * k;
+            t[k] = idx < count ? load(idx) : 0.f;
+        }
+#pragma unroll
+        for (int k = 0; k < CHUNK; ++k) {
+            const int idx = base + 64 * k;
+            if (idx < count) store(idx, t[k]);
+        }
+    }
+}
+constexpr int copy_chunk(int elements_per_wavefront) {
+    return elements_per_wavefront >= 1024 ? 16 : (elements_per_wavefront <= 64 ? 1 : (elements_per_wavefront + 63) / 64);
+}
+
 enum Stage { kFull = 0, kTridiagOnly = 1, kQrOnly = 2, kSpectral = 3, kQrPartial = 4 };
 enum SpectralFn { kFnSqrt = 0, kFnInvSqrt = 1 };
 

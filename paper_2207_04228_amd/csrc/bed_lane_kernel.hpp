@@ -67,10 +67,12 @@ __global__ __launch_bounds__(64) void lane_kernel(KernelArgs args) {
     {
         const float* __restrict__ Ab = args.A + b0 * nn;
         const float rcp = 1.0f / (float)nn;
-        for (int idx = lane; idx < nb * nn; idx += 64) {
-            const int m = (int)(((float)idx + 0.5f) * rcp);
-            stage[m * MS + (idx - m * nn)] = Ab[idx];
-        }
+        chunked_copy<16>(
+            nb * nn, lane, [&](int idx) { return Ab[idx]; },
+            [&](int idx, float x) {
+                const int m = (int)(((float)idx + 0.5f) * rcp);
+                stage[m * MS + (idx - m * nn)] = x;
+            });
     }
     __syncthreads();
 
@@ -351,10 +353,13 @@ __global__ __launch_bounds__(64) void lane_kernel(KernelArgs args) {
         __syncthreads();
         float* __restrict__ Fb = args.fn_out + b0 * nn;
         const float rcp = 1.0f / (float)nn;
-        for (int idx = lane; idx < nb * nn; idx += 64) {
-            const int m = (int)(((float)idx + 0.5f) * rcp);
-            Fb[idx] = stage[m * MS + (idx - m * nn)];
-        }
+        chunked_copy<16>(
+            nb * nn, lane,
+            [&](int idx) {
+                const int m = (int)(((float)idx + 0.5f) * rcp);
+                return stage[m * MS + (idx - m * nn)];
+            },
+            [&](int idx, float x) { Fb[idx] = x; });
     }
     if (WANT_V && STAGE == kFull) {
         __syncthreads();
@@ -369,10 +374,13 @@ __global__ __launch_bounds__(64) void lane_kernel(KernelArgs args) {
         __syncthreads();
         float* __restrict__ Vb = args.evecs + b0 * nn;
         const float rcp = 1.0f / (float)nn;
-        for (int idx = lane; idx < nb * nn; idx += 64) {
-            const int m = (int)(((float)idx + 0.5f) * rcp);
-            Vb[idx] = stage[m * MS + (idx - m * nn)];
-        }
+        chunked_copy<16>(
+            nb * nn, lane,
+            [&](int idx) {
+                const int m = (int)(((float)idx + 0.5f) * rcp);
+                return stage[m * MS + (idx - m * nn)];
+            },
+            [&](int idx, float x) { Vb[idx] = x; });
     }
     if (mine) {
         if (args.info) args.info[b0 + lane] = info;

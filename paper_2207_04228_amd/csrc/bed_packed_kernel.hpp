@@ -221,12 +221,14 @@ __global__ __launch_bounds__(64) void packed_kernel(KernelArgs args) {
     {
         const float* __restrict__ Ab = args.A + m0 * nn;
         const float rcp_nn = 1.0f / (float)nn, rcp_n = 1.0f / (float)n;
-        for (int idx = lane; idx < cnt * nn; idx += 64) {
-            const int m = (int)(((float)idx + 0.5f) * rcp_nn);
-            const int rem = idx - m * nn;
-            const int i = (int)(((float)rem + 0.5f) * rcp_n);
-            sV_all[m * VA + i * LD + (rem - i * n)] = Ab[idx];
-        }
+        chunked_copy<copy_chunk(PER_WAVE * N * N)>(
+            cnt * nn, lane, [&](int idx) { return Ab[idx]; },
+            [&](int idx, float x) {
+                const int m = (int)(((float)idx + 0.5f) * rcp_nn);
+                const int rem = idx - m * nn;
+                const int i = (int)(((float)rem + 0.5f) * rcp_n);
+                sV_all[m * VA + i * LD + (rem - i * n)] = x;
+            });
     }
     wave_sync();
     float a[N], v[N];
@@ -568,13 +570,15 @@ __global__ __launch_bounds__(64) void packed_kernel(KernelArgs args) {
     if (WANT_V && STAGE == kFull) {
         float* __restrict__ Vb = args.evecs + m0 * nn;
         const float rcp_nn = 1.0f / (float)nn, rcp_n = 1.0f / (float)n;
-        for (int idx = lane; idx < cnt * nn; idx += 64) {
-            const int m = (int)(((float)idx + 0.5f) * rcp_nn);
-            const int rem = idx - m * nn;
-            const int i = (int)(((float)rem + 0.5f) * rcp_n);
-            const int j = rem - i * n;
-            Vb[idx] = sV_all[m * VA + sI_all[m * GW + j] * LD + i];
-        }
+        chunked_copy<copy_chunk(PER_WAVE * N * N)>(
+            cnt * nn, lane,
+            [&](int idx) {
+                const int m = (int)(((float)idx + 0.5f) * rcp_nn);
+                const int rem = idx - m * nn;
+                const int i = (int)(((float)rem + 0.5f) * rcp_n);
+                return sV_all[m * VA + sI_all[m * GW + (rem - i * n)] * LD + i];
+            },
+            [&](int idx, float x) { Vb[idx] = x; });
     }
     if (mine && r == 0) {
         if (args.info) args.info[m0 + grp] = info;

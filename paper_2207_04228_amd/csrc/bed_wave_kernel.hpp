@@ -618,11 +618,12 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         float x[N];
         const float* __restrict__ Ab = args.A + (size_t)b * n * n;
         const float rcp_n = 1.0f / (float)n;
-        for (int idx = lane; idx < n * n; idx += 64) {
-            int i = (int)(((float)idx + 0.5f) * rcp_n);
-            int j = idx - i * n;
-            sV[i * LD + j] = Ab[idx];
-        }
+        chunked_copy<copy_chunk(N * N)>(
+            n * n, lane, [&](int idx) { return Ab[idx]; },
+            [&](int idx, float x) {
+                const int i = (int)(((float)idx + 0.5f) * rcp_n);
+                sV[i * LD + (idx - i * n)] = x;
+            });
         wave_sync();
         float amax = 0.f;
 #pragma unroll
@@ -694,11 +695,12 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         // ---- load: coalesced into LDS, then row `row` (lower triangle mirrored)
         const float* __restrict__ Ab = args.A + (size_t)b * n * n;
         const float rcp_n = 1.0f / (float)n;
-        for (int idx = lane; idx < n * n; idx += 64) {
-            int i = (int)(((float)idx + 0.5f) * rcp_n);
-            int j = idx - i * n;
-            sV[i * LD + j] = Ab[idx];
-        }
+        chunked_copy<copy_chunk(N * N)>(
+            n * n, lane, [&](int idx) { return Ab[idx]; },
+            [&](int idx, float x) {
+                const int i = (int)(((float)idx + 0.5f) * rcp_n);
+                sV[i * LD + (idx - i * n)] = x;
+            });
         wave_sync();
         float amax = 0.f;
 #pragma unroll
@@ -831,11 +833,13 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         if (WANT_V) {
             float* __restrict__ Vb = args.evecs + (size_t)b * n * n;
             const float rcp_n = 1.0f / (float)n;
-            for (int idx = lane; idx < n * n; idx += 64) {
-                int i = (int)(((float)idx + 0.5f) * rcp_n);
-                int j = idx - i * n;
-                Vb[idx] = sV[j * LD + i];
-            }
+            chunked_copy<copy_chunk(N * N)>(
+                n * n, lane,
+                [&](int idx) {
+                    const int i = (int)(((float)idx + 0.5f) * rcp_n);
+                    return sV[(idx - i * n) * LD + i];
+                },
+                [&](int idx, float x) { Vb[idx] = x; });
         }
     } else {
         // ---- shifted QR iterations on the tridiagonal in sP ----
@@ -852,11 +856,13 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
             if (WANT_V) {
                 float* __restrict__ Vb = args.evecs + (size_t)b * n * n;
                 const float rcp_n = 1.0f / (float)n;
-                for (int idx = lane; idx < n * n; idx += 64) {
-                    int i = (int)(((float)idx + 0.5f) * rcp_n);
-                    int j = idx - i * n;
-                    Vb[idx] = sV[j * LD + i];
-                }
+                chunked_copy<copy_chunk(N * N)>(
+                    n * n, lane,
+                    [&](int idx) {
+                        const int i = (int)(((float)idx + 0.5f) * rcp_n);
+                        return sV[(idx - i * n) * LD + i];
+                    },
+                    [&](int idx, float x) { Vb[idx] = x; });
             }
             if (lane == 0 && args.rotations) args.rotations[b] = rotations;
             return;
@@ -901,11 +907,13 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
         }
 
         // ---- ascending order: rank of d[lane] among d[0..n) ----
+        // (lane j holds d[j]: the keys come from v_readlane, not from a chain of LDS round trips)
         const uint32_t mykey = sort_key(dl);
         int rank = 0;
-        for (int j = 0; j < n; ++j) {
-            const uint32_t kj = sort_key(sP[j].y);
-            rank += (kj < mykey || (kj == mykey && j < lane)) ? 1 : 0;
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const uint32_t kj = (uint32_t)__builtin_amdgcn_readlane((int)mykey, j);
+            rank += (j < n && (kj < mykey || (kj == mykey && j < lane))) ? 1 : 0;
         }
         if (lane < n) args.evals[(size_t)b * n + rank] = dl * inv_scale;
         if (WANT_V) {
@@ -914,11 +922,13 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
             wave_sync();
             float* __restrict__ Vb = args.evecs + (size_t)b * n * n;
             const float rcp_n = 1.0f / (float)n;
-            for (int idx = lane; idx < n * n; idx += 64) {
-                int i = (int)(((float)idx + 0.5f) * rcp_n);
-                int j = idx - i * n;
-                Vb[idx] = sV[sinv[j] * LD + i];
-            }
+            chunked_copy<copy_chunk(N * N)>(
+                n * n, lane,
+                [&](int idx) {
+                    const int i = (int)(((float)idx + 0.5f) * rcp_n);
+                    return sV[sinv[idx - i * n] * LD + i];
+                },
+                [&](int idx, float x) { Vb[idx] = x; });
         }
     }
 

@@ -34,7 +34,8 @@ def build_profiling_library() -> str:
 
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser()
-    ap.add_argument("--n", type=int, default=32, choices=[4, 8, 16, 32])
+    ap.add_argument("--n", type=int, default=32, choices=[4, 8, 16, 32, 64],
+                    help="4..32: the batch-512 input of the benchmark; 64: config 5 (batch 256, clustered spectrum)")
     ap.add_argument("--build-only", action="store_true")
     a = ap.parse_args(argv)
     if a.build_only or not os.path.exists(LIB):
@@ -48,7 +49,7 @@ def main(argv=None) -> int:
     vp, ci = ctypes.c_void_p, ctypes.c_int
     lib.bed_phase_profile.argtypes = [vp, ci, ci, vp, vp, vp, vp]
     lib.bed_phase_profile.restype = ci
-    A32 = dict(workloads.headline_points())[a.n]
+    A32 = workloads.config5(64) if a.n == 64 else dict(workloads.headline_points())[a.n]
     dev = torch.device("cuda:0")
     A = torch.from_numpy(A32).to(dev)
     batch, n = A.shape[0], a.n
