@@ -194,6 +194,8 @@ __global__ __launch_bounds__(64) void lane_kernel(KernelArgs args) {
 #pragma unroll
         for (int k = 0; k < N - 1; ++k) {
             const bool act = (k >= lo) && (k < hi);
+            // a position outside the window of every lane of the wavefront changes nothing
+            if (__ballot(act) == 0) continue;
             const bool first = (k == lo);
             g = first ? (d[k] - mu) : g;
             const float ek = e[k];
