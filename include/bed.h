@@ -111,6 +111,8 @@ int bed_syevd_info(const float* A, int batch, int n, float* evals, float* evecs,
  *                      for 16 < n <= 32
  *   BED_FAMILY_LANE    one matrix per lane, n <= 8
  *   BED_FAMILY_BLOCK   four wavefronts per matrix, 64 < n <= 128
+ *   BED_FAMILY_PAIR    two wavefronts per matrix, 32 < n <= 64, eigenvectors required
+ *                      (BED_ERR_NULL without evecs)
  * BED_ERR_N if the family does not serve this n, BED_ERR_ARG for an unknown family.
  */
 typedef enum {
@@ -118,7 +120,8 @@ typedef enum {
     BED_FAMILY_WAVE = 1,
     BED_FAMILY_PACKED = 2,
     BED_FAMILY_LANE = 3,
-    BED_FAMILY_BLOCK = 4
+    BED_FAMILY_BLOCK = 4,
+    BED_FAMILY_PAIR = 5
 } bed_family;
 int bed_syevd_family(const float* A, int batch, int n, float* evals, float* evecs, int* info,
                      unsigned* rotations, int family, void* stream);
@@ -310,8 +313,9 @@ int bed_ceiling_copy(const float* src, float* dst, size_t count, int blocks, voi
 /*
  * Name of the kernel that bed_syevd (want_vectors = 1) or its eigenvalues-only form
  * (want_vectors = 0) launches for this batch and n, e.g. "wave_kernel<32>" (one wavefront per
- * matrix, register arrays of 32), "lane_kernel<4>" (one matrix per lane), "block_kernel" (four
- * wavefronts per matrix); static storage, NULL for arguments out of range.
+ * matrix, register arrays of 32), "packed_kernel<16>" (several matrices per wavefront),
+ * "lane_kernel<4>" (one matrix per lane), "pair_kernel<64>" (two wavefronts per matrix),
+ * "block_kernel" (four wavefronts per matrix); static storage, NULL for arguments out of range.
  */
 const char* bed_kernel_variant(int batch, int n, int want_vectors);
 

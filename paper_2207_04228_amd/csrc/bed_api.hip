@@ -91,7 +91,8 @@ int bed_syevd_family(const float* A, int batch, int n, float* evals, float* evec
                      unsigned* rotations, int family, void* stream) {
     int st = check_common(batch, n);
     if (st != BED_OK) return st;
-    if (family < BED_FAMILY_AUTO || family > BED_FAMILY_BLOCK) return BED_ERR_ARG;
+    if (family < BED_FAMILY_AUTO || family > BED_FAMILY_PAIR) return BED_ERR_ARG;
+    if (family == BED_FAMILY_PAIR && !evecs) return BED_ERR_NULL;
     if (!bed::family_serves(family, n)) return BED_ERR_N;
     if (batch == 0) return BED_OK;
     if (!A || !evals) return BED_ERR_NULL;
@@ -291,9 +292,8 @@ int bed_syevd_lockstep_static(const float* A, int batch, int n, float epsilon, i
 }
 
 const char* bed_kernel_variant(int batch, int n, int want_vectors) {
-    (void)want_vectors;   // the eigenvalues-only form runs the same kernel family with the V part compiled out
     if (batch < 0 || n < 1 || n > BED_MAX_N) return nullptr;
-    return bed::kernel_variant(batch, n);
+    return bed::kernel_variant(batch, n, want_vectors != 0);
 }
 
 const char* bed_status_string(int status) {

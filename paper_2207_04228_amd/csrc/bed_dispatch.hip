@@ -5,6 +5,7 @@ namespace bed {
 
 hipError_t launch_lane(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_packed(const KernelArgs&, int, bool, hipStream_t);
+hipError_t launch_pair(const KernelArgs&, hipStream_t);
 hipError_t launch_wave_n4(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n8(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n12(const KernelArgs&, int, bool, hipStream_t);
@@ -23,10 +24,11 @@ namespace {
 
 constexpr int kPackedFromBatch = 2560;
 constexpr int kPacked32FromBatch = 4096;
+constexpr int kPairUpToBatch = 512;
 constexpr int kLane4FromBatch = 20480;
 constexpr int kLane8FromBatch = 32768;
 
-enum Family { kLaneFamily, kPackedFamily, kWaveFamily, kBlockFamily };
+enum Family { kLaneFamily, kPackedFamily, kWaveFamily, kPairFamily, kBlockFamily };
 struct Choice {
     Family family;
     int N;               // register-array size of the instantiation (0 for the block kernel)
@@ -37,7 +39,7 @@ Choice wave_choice(int n);
 
 // The one place that decides which kernel serves a problem.  `forced` (kFamilyAuto unless a test
 // or a measurement asks for one family) must be able to serve n: the caller has checked.
-Choice choose(int batch, int n, int stage, int forced) {
+Choice choose(int batch, int n, int stage, bool want_v, int forced) {
     if (forced == kFamilyLane) return n <= 4 ? Choice{kLaneFamily, 4, "lane_kernel<4>"} : Choice{kLaneFamily, 8, "lane_kernel<8>"};
     if (forced == kFamilyPacked) {
         if (n <= 4) return {kPackedFamily, 4, "packed_kernel<4>"};
@@ -48,6 +50,7 @@ Choice choose(int batch, int n, int stage, int forced) {
         return {kPackedFamily, 32, "packed_kernel<32>"};
     }
     if (forced == kFamilyWave) return wave_choice(n);
+    if (forced == kFamilyPair) return {kPairFamily, 0, n <= 40 ? "pair_kernel<40>" : n <= 48 ? "pair_kernel<48>" : n <= 56 ? "pair_kernel<56>" : "pair_kernel<64>"};
     if (forced == kFamilyBlock) return {kBlockFamily, 0, "block_kernel"};
     // Measured crossovers on MI355X (us per launch, eigenvectors on; wave / packed / lane):
     //   n = 4:  batch 2048: 8.4 / 8.6 / 13.0   4096: 11.5 / 9.1 / 13.7   16384: 27.7 / 13.2 / 14.2   32768: 49 / 21.7 / 14.9
@@ -64,10 +67,14 @@ Choice choose(int batch, int n, int stage, int forced) {
     const bool whole = (stage == kFull || stage == kSpectral);
     if (whole && n <= 4 && batch >= kLane4FromBatch) return {kLaneFamily, 4, "lane_kernel<4>"};
     if (whole && n <= 8 && batch >= kLane8FromBatch) return {kLaneFamily, 8, "lane_kernel<8>"};
-    if (whole && n <= 16 && batch >= kPackedFromBatch) return choose(batch, n, stage, kFamilyPacked);
+    if (whole && n <= 16 && batch >= kPackedFromBatch) return choose(batch, n, stage, want_v, kFamilyPacked);
     // two matrices per wavefront for 16 < n <= 32: a smaller gain (the one-wavefront kernel already
     // serves both sweeps of such a matrix with one instruction stream), from a larger batch
-    if (whole && n <= 32 && batch >= kPacked32FromBatch) return choose(batch, n, stage, kFamilyPacked);
+    if (whole && n <= 32 && batch >= kPacked32FromBatch) return choose(batch, n, stage, want_v, kFamilyPacked);
+    // 32 < n <= 64 with eigenvectors while the chip is mostly idle: two wavefronts per matrix
+    // (us per launch, wave / pair: n = 48: batch 256: 175 / 165, 512: 179 / 168, 768: 179 / 203;
+    //  n = 64: batch 256: 285 / 274, 512: 293 / 274, 768: 290 / 327)
+    if (stage == kFull && want_v && n > 32 && n <= 64 && batch <= kPairUpToBatch) return choose(batch, n, stage, want_v, kFamilyPair);
     if (n <= 64) return wave_choice(n);
     return {kBlockFamily, 0, "block_kernel"};     // 64 < n <= 128: four wavefronts per matrix
 }
@@ -89,7 +96,7 @@ Choice wave_choice(int n) {
 
 }  // namespace
 
-const char* kernel_variant(int batch, int n) { return choose(batch, n, kFull, kFamilyAuto).name; }
+const char* kernel_variant(int batch, int n, bool want_v) { return choose(batch, n, kFull, want_v, kFamilyAuto).name; }
 
 bool family_serves(int family, int n) {
     switch (family) {
@@ -98,13 +105,18 @@ bool family_serves(int family, int n) {
         case kFamilyPacked: return n >= 1 && n <= 32;
         case kFamilyLane: return n >= 1 && n <= 8;
         case kFamilyBlock: return n > 64 && n <= 128;
+        case kFamilyPair: return n > 32 && n <= 64;
         default: return false;
     }
 }
 
 hipError_t launch(const KernelArgs& args, int stage, bool want_v, hipStream_t stream, int forced) {
     if (args.batch == 0) return hipSuccess;
-    const Choice c = choose(args.batch, args.n, stage, forced);
+    const Choice c = choose(args.batch, args.n, stage, want_v, forced);
+    if (c.family == kPairFamily) {
+        if (!want_v || stage != kFull) return hipErrorInvalidValue;     // the pair kernels always form eigenvectors
+        return launch_pair(args, stream);
+    }
     if (c.family == kLaneFamily) return launch_lane(args, stage, want_v, stream);
     if (c.family == kPackedFamily) return launch_packed(args, stage, want_v, stream);
     if (c.family == kBlockFamily) return launch_block(args, stage, want_v, stream);

@@ -110,10 +110,10 @@ constexpr size_t kLockstepScratchBytes = 1u << 20;
 hipError_t lockstep_scratch(void** ptr);
 
 // Name of the kernel that serves a full decomposition of this batch and n.
-const char* kernel_variant(int batch, int n);
+const char* kernel_variant(int batch, int n, bool want_v);
 
 // Kernel families (values of bed_family in bed.h).
-enum FamilyId { kFamilyAuto = 0, kFamilyWave = 1, kFamilyPacked = 2, kFamilyLane = 3, kFamilyBlock = 4 };
+enum FamilyId { kFamilyAuto = 0, kFamilyWave = 1, kFamilyPacked = 2, kFamilyLane = 3, kFamilyBlock = 4, kFamilyPair = 5 };
 bool family_serves(int family, int n);
 
 // Enqueue one launch; returns the status of that launch.  `forced`: a family other than

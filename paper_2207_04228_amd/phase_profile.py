@@ -34,8 +34,10 @@ def build_profiling_library() -> str:
 
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser()
-    ap.add_argument("--n", type=int, default=32, choices=[4, 8, 16, 32, 64],
-                    help="4..32: the batch-512 input of the benchmark; 64: config 5 (batch 256, clustered spectrum)")
+    ap.add_argument("--n", type=int, default=32, choices=[4, 8, 16, 32, 48, 64],
+                    help="4..32: the batch-512 input of the benchmark; 48, 64: config 5 (batch 256, clustered spectrum)")
+    ap.add_argument("--family", type=int, default=1, choices=[1, 5],
+                    help="1: one wavefront per matrix; 5: two wavefronts per matrix (n = 48, 64)")
     ap.add_argument("--build-only", action="store_true")
     a = ap.parse_args(argv)
     if a.build_only or not os.path.exists(LIB):
@@ -47,9 +49,9 @@ def main(argv=None) -> int:
     from . import binding, workloads
     lib = ctypes.CDLL(LIB)
     vp, ci = ctypes.c_void_p, ctypes.c_int
-    lib.bed_phase_profile.argtypes = [vp, ci, ci, vp, vp, vp, vp]
+    lib.bed_phase_profile.argtypes = [vp, ci, ci, vp, vp, vp, ci, vp]
     lib.bed_phase_profile.restype = ci
-    A32 = workloads.config5(64) if a.n == 64 else dict(workloads.headline_points())[a.n]
+    A32 = workloads.config5(a.n) if a.n >= 48 else dict(workloads.headline_points())[a.n]
     dev = torch.device("cuda:0")
     A = torch.from_numpy(A32).to(dev)
     batch, n = A.shape[0], a.n
@@ -60,7 +62,7 @@ def main(argv=None) -> int:
 
     def call():
         st = lib.bed_phase_profile(binding._ptr(A), batch, n, binding._ptr(ev), binding._ptr(V), binding._ptr(ph),
-                                   ctypes.c_void_p(stream.cuda_stream))
+                                   a.family, ctypes.c_void_p(stream.cuda_stream))
         assert st == 0, st
 
     def timed(fn, reps=50):
@@ -76,14 +78,14 @@ def main(argv=None) -> int:
 
     t_instr = timed(call)
     ev2, V2 = torch.empty_like(ev), torch.empty_like(V)
-    t_prod = timed(lambda: binding.bed_syevd_info(A, ev2, V2, family=binding.BED_FAMILY_WAVE))
+    t_prod = timed(lambda: binding.bed_syevd_info(A, ev2, V2, family=a.family))
     assert torch.equal(ev, ev2) and torch.equal(V, V2), "the profiling build must compute the same result"
-    _, _, _, rot = binding.bed_syevd_info(A, ev2, V2, family=binding.BED_FAMILY_WAVE)
+    _, _, _, rot = binding.bed_syevd_info(A, ev2, V2, family=a.family)
     p = ph.cpu().numpy().astype(np.float64)
     rot = rot.cpu().numpy().astype(np.float64)
     total = p[:, :7].sum(axis=1)
     last = int(np.argmax(total))
-    print(f"n = {n}, batch {batch}: product launch {t_prod:.1f} us, instrumented launch {t_instr:.1f} us "
+    print(f"n = {n}, batch {batch}, {'one wavefront' if a.family == 1 else 'two wavefronts'} per matrix: product launch {t_prod:.1f} us, instrumented launch {t_instr:.1f} us "
           f"(events around a loop of 50 launches)")
     print(f"rotations per matrix: mean {rot.mean():.0f}, slowest wavefront {rot[last]:.0f}; "
           f"shader clock cycles per wavefront (s_memtime):\n")

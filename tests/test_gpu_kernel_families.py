@@ -134,3 +134,63 @@ def test_family_argument_checks():
     with pytest.raises(binding.BedError) as e:
         binding.bed_syevd_info(A, family=9)
     assert e.value.status == -7
+
+
+PAIR = 5
+
+
+@pytest.mark.parametrize("n", [33, 36, 40, 41, 47, 48, 49, 56, 57, 63, 64])
+def test_pair_kernel_every_size_class(n):
+    """Two wavefronts per matrix (32 < n <= 64): odd and even batch sizes (a workgroup holds two
+    matrices), indefinite input."""
+    rng = np.random.default_rng(8500 + n)
+    for batch in (1, 2, 5, 64):
+        A = rng.standard_normal((batch, n, n))
+        A = (0.5 * (A + A.transpose(0, 2, 1))).astype(np.float32)
+        print(f"[family] pair n={n} batch={batch}", flush=True)
+        from oracle import jacobi
+        from oracle.acceptance import evaluate
+        lam_o, V_o = jacobi.syevd(A)
+        lam_g, V_g, info, rot = _solve(A, PAIR)
+        assert np.all(info == 0)
+        assert evaluate(A, lam_g, V_g, lam_o, V_o).passes()
+        lam_w, V_w, info_w, rot_w = _solve(A, WAVE)
+        assert np.array_equal(rot, rot_w)            # same shifts, same deflation decisions
+
+
+def test_pair_kernel_on_config5_and_structured_input():
+    from oracle import jacobi
+    from oracle.acceptance import evaluate
+    from paper_2207_04228_amd import binding, workloads
+    for n in (48, 64):
+        A = workloads.config5(n)
+        assert binding.bed_kernel_variant(A.shape[0], n) == f"pair_kernel<{n}>"
+        lam_o, V_o = jacobi.syevd(A)
+        lam_g, V_g, info, rot = _solve(A, 0)
+        acc = evaluate(A, lam_g, V_g, lam_o, V_o)
+        print(f"[family] pair config5 n={n}: {acc.worst()}", flush=True)
+        assert np.all(info == 0) and acc.passes()
+    for n in (33, 47, 64):
+        for name, A in workloads.structured_cases(n, 7, seed=900 + n):
+            lam_o, V_o = jacobi.syevd(A)
+            lam_g, V_g, info, rot = _solve(A, PAIR)
+            assert np.all((info & 0xFFFF) == 0), (n, name)
+            assert evaluate(A, lam_g, V_g, lam_o, V_o).passes(), (n, name)
+
+
+def test_pair_kernel_nan_and_argument_checks():
+    import torch
+    from paper_2207_04228_amd import binding, workloads
+    A = workloads.config5(48, batch=5).copy()
+    A[2, 7, 3] = np.nan
+    lam, V, info, rot = _solve(A, PAIR)
+    good = [0, 1, 3, 4]
+    assert np.isfinite(lam[good]).all() and np.isfinite(V[good]).all() and np.all(info[good] == 0)
+    assert info[2] > 0 and not np.isfinite(lam[2]).all()
+    At = torch.from_numpy(A).to("cuda:0")
+    with pytest.raises(binding.BedError) as e:
+        binding.bed_syevd_info(At, want_vectors=False, family=PAIR)      # the pair kernels always form eigenvectors
+    assert e.value.status == -1
+    with pytest.raises(binding.BedError) as e:
+        binding.bed_syevd_info(At[:, :32, :32].contiguous(), family=PAIR)
+    assert e.value.status == -3

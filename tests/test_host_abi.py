@@ -86,6 +86,10 @@ def test_argument_validation_is_host_side(lib):
     assert binding.bed_kernel_variant(4096, 32) == "packed_kernel<32>"
     assert binding.bed_kernel_variant(4096, 33) == "wave_kernel<40>"
     assert binding.bed_kernel_variant(256, 100) == "block_kernel"
+    assert binding.bed_kernel_variant(256, 64) == "pair_kernel<64>"
+    assert binding.bed_kernel_variant(256, 64, want_vectors=False) == "wave_kernel<64>"
+    assert binding.bed_kernel_variant(513, 64) == "wave_kernel<64>"
+    assert binding.bed_kernel_variant(256, 33) == "pair_kernel<40>"
     assert lib.bed_kernel_variant(1, 129, 1) is None
     f = ctypes.c_float
     assert lib.bed_spd_fn(None, 1, 4, 0, f(0.0), V, None, None, None) == -1        # NULL A
