@@ -384,13 +384,13 @@ def main(argv=None) -> int:
     # n = 4 and n = 8 go up to 2^20 matrices (config 2 / config 3 inputs, tiled beyond 65536) so that
     # the rate with every SIMD holding several wavefronts is on record.
     big = ((4, 4096), (4, 65536), (4, 1 << 18), (4, 1 << 20), (8, 4096), (8, 65536), (8, 1 << 18), (8, 1 << 20),
-           (16, 4096), (16, 65536), (32, 4096), (32, 16384), (64, 256), (128, 256))
+           (16, 4096), (16, 65536), (32, 4096), (32, 16384), (48, 256), (64, 256), (128, 256))
     for n, batch in (() if a.no_extras else big):
         base = min(batch, 65536)
         A32b = (workloads.config2(base) if n == 4 else
                 workloads.config4(batch=base) if n == 16 else
                 workloads.config3(n, batch=base) if n <= 32 else
-                workloads.config5(n, batch=base) if n == 64 else workloads.covariance(base, n, 4 * n, 1e-4, 1))
+                workloads.config5(n, batch=base) if n in (48, 64) else workloads.covariance(base, n, 4 * n, 1e-4, 1))
         Ab = torch.from_numpy(A32b).to(dev)
         if batch > base:
             Ab = Ab.repeat(batch // base, 1, 1).contiguous()

@@ -207,10 +207,10 @@ __global__ __launch_bounds__(256) void pair_kernel(KernelArgs args) {
         const float dl = d_lane[0];
         const uint32_t mykey = sort_key(dl);
         int rank = 0;
-#pragma unroll
-        for (int j = 0; j < N; ++j) {
-            const uint32_t kj = (uint32_t)__builtin_amdgcn_readlane((int)mykey, j);
-            rank += (j < n && (kj < mykey || (kj == mykey && j < lane))) ? 1 : 0;
+        const float2* const sPa = sP_all + wv * PA;
+        for (int j = 0; j < n; ++j) {
+            const uint32_t kj = sort_key(sPa[j].y);
+            rank += (kj < mykey || (kj == mykey && j < lane)) ? 1 : 0;
         }
         if (mine && lane < n) {
             args.evals[(size_t)m * n + rank] = dl * inv_scale;
