@@ -101,6 +101,24 @@ int bed_syevd_info(const float* A, int batch, int n, float* evals, float* evecs,
                    int* info, unsigned* rotations, void* stream);
 
 /*
+ * bed_syevd_info with the two run-time constants of the paper's procedure exposed (App. B
+ * "Implementation Details": threshold 1e-5, a fixed number of iterations):
+ *   epsilon_abs  > 0: the deflation test of the paper as written, |e_k| <= epsilon_abs, an ABSOLUTE
+ *                threshold in the units of A (Sec. 3.2.3; the paper uses 1e-5), applied to every
+ *                off-diagonal of the active window after each outer iteration, per matrix.  Each
+ *                deflated entry perturbs the eigenvalues by at most epsilon_abs, whatever ||A||:
+ *                for ||A||_2 near 1 that is at the edge of the 1e-5 ||A||_2 accuracy bar, for small
+ *                ||A|| it is far outside.  0: the library's relative test (bed_syevd_info).
+ *                Finite and >= 0, else BED_ERR_ARG.
+ *   sweep_cap    > 0: at most this many QR sweeps per matrix (two per outer iteration; App. B runs
+ *                n outer iterations, i.e. 2 n sweeps); off-diagonals still live then are counted in
+ *                info.  0: the default cap of 30 n.  < 0: BED_ERR_ARG.
+ * Everything else as bed_syevd_info.
+ */
+int bed_syevd_tol(const float* A, int batch, int n, float* evals, float* evecs, int* info,
+                  unsigned* rotations, float epsilon_abs, int sweep_cap, void* stream);
+
+/*
  * bed_syevd_info through ONE kernel family, whatever the batch size (for parity tests of every
  * family at every batch size, and for measuring the batch sizes at which the automatic choice
  * should change).  Same method, arguments and outputs; the families differ in how matrices

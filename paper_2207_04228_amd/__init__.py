@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     bed_syevd,
     bed_syevd_info,
     bed_syevd_lockstep,
+    bed_syevd_tol,
     bed_syevd_lockstep_static,
     bed_syevd_lockstep_static_capacity,
     bed_tridiag,

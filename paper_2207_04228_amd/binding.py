@@ -46,6 +46,8 @@ def load_library():
         lib.bed_syevd_info.restype = ci
         lib.bed_syevd_family.argtypes = [vp, ci, ci, vp, vp, vp, vp, ci, vp]
         lib.bed_syevd_family.restype = ci
+        lib.bed_syevd_tol.argtypes = [vp, ci, ci, vp, vp, vp, vp, ctypes.c_float, ci, vp]
+        lib.bed_syevd_tol.restype = ci
         lib.bed_tridiag.argtypes = [vp, ci, ci, vp, vp, vp, vp]
         lib.bed_tridiag.restype = ci
         lib.bed_tridiag_qr.argtypes = [vp, vp, ci, ci, vp, vp, vp, vp, vp]
@@ -201,6 +203,23 @@ def bed_syevd_info(A, evals=None, evecs=None, *, want_vectors=True, stream=None,
                                          _ptr(info), _ptr(rot), int(family), _stream(stream))
     if st != 0:
         raise BedError(st, "bed_syevd_info")
+    return evals, evecs, info, rot
+
+
+def bed_syevd_tol(A, epsilon_abs=0.0, sweep_cap=0, *, want_vectors=True, stream=None):
+    """bed_syevd_info with the paper's absolute deflation threshold (epsilon_abs > 0; App. B: 1e-5) and / or
+    a cap on the number of sweeps.  Returns (evals, evecs or None, info, rotations)."""
+    import torch
+    _check_dev(A, "A", torch.float32)
+    batch, n = _square_batch(A)
+    evals = torch.empty((batch, n), dtype=torch.float32, device=A.device)
+    evecs = torch.empty((batch, n, n), dtype=torch.float32, device=A.device) if want_vectors else None
+    info = torch.empty((batch,), dtype=torch.int32, device=A.device)
+    rot = torch.empty((batch,), dtype=torch.int32, device=A.device)
+    st = load_library().bed_syevd_tol(_ptr(A), batch, n, _ptr(evals), _ptr(evecs), _ptr(info), _ptr(rot),
+                                      float(epsilon_abs), int(sweep_cap), _stream(stream))
+    if st != 0:
+        raise BedError(st, "bed_syevd_tol")
     return evals, evecs, info, rot
 
 

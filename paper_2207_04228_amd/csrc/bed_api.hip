@@ -21,6 +21,9 @@ int check_common(int batch, int n) {
     return BED_OK;
 }
 
+int syevd_checked(const float* A, int batch, int n, float* evals, float* evecs, int* info, unsigned* rotations,
+                  int family, float epsilon_abs, int sweep_cap, void* stream);
+
 int run(const bed::KernelArgs& args, int stage, bool want_v, void* stream, int family = bed::kFamilyAuto) {
     if (args.batch == 0) return BED_OK;
     hipError_t err = bed::launch(args, stage, want_v, static_cast<hipStream_t>(stream), family);
@@ -89,6 +92,24 @@ int bed_syevd_info(const float* A, int batch, int n, float* evals, float* evecs,
 
 int bed_syevd_family(const float* A, int batch, int n, float* evals, float* evecs, int* info,
                      unsigned* rotations, int family, void* stream) {
+    return syevd_checked(A, batch, n, evals, evecs, info, rotations, family, 0.f, 0, stream);
+}
+
+int bed_syevd_tol(const float* A, int batch, int n, float* evals, float* evecs, int* info,
+                  unsigned* rotations, float epsilon_abs, int sweep_cap, void* stream) {
+    if (!(epsilon_abs >= 0.f) || !(epsilon_abs < __builtin_inff()) || sweep_cap < 0) {
+        int st = check_common(batch, n);
+        return st != BED_OK ? st : BED_ERR_ARG;
+    }
+    return syevd_checked(A, batch, n, evals, evecs, info, rotations, BED_FAMILY_AUTO, epsilon_abs, sweep_cap, stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+int syevd_checked(const float* A, int batch, int n, float* evals, float* evecs, int* info, unsigned* rotations,
+                  int family, float epsilon_abs, int sweep_cap, void* stream) {
     int st = check_common(batch, n);
     if (st != BED_OK) return st;
     if (family < BED_FAMILY_AUTO || family > BED_FAMILY_PAIR) return BED_ERR_ARG;
@@ -109,8 +130,14 @@ int bed_syevd_family(const float* A, int batch, int n, float* evals, float* evec
     args.rotations = rotations;
     args.batch = batch;
     args.n = n;
+    args.abs_eps = epsilon_abs;
+    args.sweep_cap = (uint32_t)sweep_cap;
     return run(args, bed::kFull, evecs != nullptr, stream, family);
 }
+
+}  // namespace
+
+extern "C" {
 
 int bed_syevd(const float* A, int batch, int n, float* evals, float* evecs, void* stream) {
     return bed_syevd_info(A, batch, n, evals, evecs, nullptr, nullptr, stream);

@@ -44,6 +44,9 @@ constexpr int copy_chunk(int elements_per_wavefront) {
     return elements_per_wavefront >= 1024 ? 16 : (elements_per_wavefront <= 64 ? 1 : (elements_per_wavefront + 63) / 64);
 }
 
+// 1 / x for x an exact power of two in [2^-125, 2^126] (the pre-scaling factors), bit-exact.
+__device__ __forceinline__ float pow2_reciprocal(float x) { return __uint_as_float(0x7F000000u - __float_as_uint(x)); }
+
 enum Stage { kFull = 0, kTridiagOnly = 1, kQrOnly = 2, kSpectral = 3, kQrPartial = 4 };
 enum SpectralFn { kFnSqrt = 0, kFnInvSqrt = 1 };
 
@@ -59,6 +62,7 @@ struct KernelArgs {
     float fn_floor;      // eigenvalues are raised to this floor before f is applied (kSpectral)
     int fn;              // SpectralFn (kSpectral)
     uint32_t sweep_cap;  // at most this many sweeps (0: the default cap of 30 n); kQrPartial stops there
+    float abs_eps;       // > 0: the paper's absolute deflation threshold on |e_k| (in units of A); 0: the relative test
     int* info;           // [batch] or nullptr
     uint32_t* rotations; // [batch] or nullptr
     unsigned long long* phases;  // [batch][8] cycle counts per phase; read only by the profiling build

@@ -54,6 +54,7 @@ __global__ __launch_bounds__(256) void pair_kernel(KernelArgs args) {
     __shared__ int sStep_all[2];            // steps published by wavefront A
     __shared__ int sFail_all[2];
     __shared__ int sInv_all[2 * 64];
+    __shared__ float sScale_all[2];         // 2^ex of the pre-scaling, for wavefront B
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -159,6 +160,7 @@ __global__ __launch_bounds__(256) void pair_kernel(KernelArgs args) {
         if (lane == 0) {
             sPa[0].x = 0.f;
             sPb[0].x = 0.f;
+            sScale_all[pr] = inv_scale;
         }
     } else {
         // ---- wavefront B: accumulation of P, one reflector behind A at most by what A has published ----
@@ -197,8 +199,9 @@ __global__ __launch_bounds__(256) void pair_kernel(KernelArgs args) {
     uint32_t rotations = 0;
     int info = 0;
     float d_lane[1];
+    const float paper_eps = args.abs_eps > 0.f ? args.abs_eps * pow2_reciprocal(sScale_all[pr]) : 0.f;
     qr_iterations<N, true, true, LD>(sP_all + wv * PA, sV, lane, 32 * (wv & 1) + (lane & 31), n, rotations, info, d_lane,
-                                     args, (int)m, clk);
+                                     args, paper_eps, clk);
     __syncthreads();       // both wavefronts of a pair leave after the same iteration; V is complete
 
     // ---- ascending order (wavefront A), then both wavefronts of the pair store ----

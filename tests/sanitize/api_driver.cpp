@@ -76,6 +76,15 @@ int main() {
     EXPECT(bed_syevd_family(A, 8, 48, L, V, I, R, BED_FAMILY_PAIR, nullptr), BED_OK);
     EXPECT(bed_syevd_family(A, 8, 16, L, V, I, R, -1, nullptr), BED_ERR_ARG);
 
+    EXPECT(bed_syevd_tol(A, 8, 16, L, V, I, R, 1e-5f, 32, nullptr), BED_OK);
+    EXPECT(bed_syevd_tol(A, 8, 16, L, V, I, R, 0.f, 0, nullptr), BED_OK);
+    EXPECT(bed_syevd_tol(A, 8, 16, L, V, I, R, -1e-5f, 0, nullptr), BED_ERR_ARG);
+    EXPECT(bed_syevd_tol(A, 8, 16, L, V, I, R, nan, 0, nullptr), BED_ERR_ARG);
+    EXPECT(bed_syevd_tol(A, 8, 16, L, V, I, R, inf, 0, nullptr), BED_ERR_ARG);
+    EXPECT(bed_syevd_tol(A, 8, 16, L, V, I, R, 1e-5f, -1, nullptr), BED_ERR_ARG);
+    EXPECT(bed_syevd_tol(A, 8, 0, L, V, I, R, -1.f, 0, nullptr), BED_ERR_N);
+    EXPECT(bed_syevd_tol(nullptr, 8, 16, L, V, I, R, 1e-5f, 0, nullptr), BED_ERR_NULL);
+
     // stage hooks
     EXPECT(bed_tridiag(A, 8, 16, L, W, V, nullptr), BED_OK);
     EXPECT(bed_tridiag(A, 8, 16, L, W, nullptr, nullptr), BED_OK);

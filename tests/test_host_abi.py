@@ -28,7 +28,7 @@ def _declared_symbols():
 
 def test_header_symbols_are_exported(lib):
     names = _declared_symbols()
-    assert {"bed_syevd", "bed_syevd_info", "bed_syevd_family", "bed_tridiag", "bed_tridiag_qr", "bed_tridiag_qr_sweeps", "bed_spd_fn", "bed_syevd_backward", "bed_spd_fn_backward", "bed_syevd_lockstep", "bed_syevd_lockstep_workspace",
+    assert {"bed_syevd", "bed_syevd_info", "bed_syevd_family", "bed_syevd_tol", "bed_tridiag", "bed_tridiag_qr", "bed_tridiag_qr_sweeps", "bed_spd_fn", "bed_syevd_backward", "bed_spd_fn_backward", "bed_syevd_lockstep", "bed_syevd_lockstep_workspace",
             "bed_status_string", "bed_version"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
