@@ -103,13 +103,16 @@ int bed_syevd_info(const float* A, int batch, int n, float* evals, float* evecs,
 /*
  * bed_syevd_info with the two run-time constants of the paper's procedure exposed (App. B
  * "Implementation Details": threshold 1e-5, a fixed number of iterations):
- *   epsilon_abs  > 0: the deflation test of the paper as written, |e_k| <= epsilon_abs, an ABSOLUTE
- *                threshold in the units of A (Sec. 3.2.3; the paper uses 1e-5), applied to every
- *                off-diagonal of the active window after each outer iteration, per matrix.  Each
- *                deflated entry perturbs the eigenvalues by at most epsilon_abs, whatever ||A||:
- *                for ||A||_2 near 1 that is at the edge of the 1e-5 ||A||_2 accuracy bar, for small
- *                ||A|| it is far outside.  0: the library's relative test (bed_syevd_info).
- *                Finite and >= 0, else BED_ERR_ARG.
+ *   epsilon_abs  > 0: the threshold of the paper, |e_k| <= epsilon_abs, ABSOLUTE in the units of A
+ *                (Sec. 3.2.3; the paper uses 1e-5), applied to every off-diagonal of the active
+ *                window after each outer iteration, per matrix.  It is used TOGETHER with the
+ *                library's relative test (an entry is negligible if it passes either), because
+ *                for ||A||_2 far above epsilon_abs / 1e-7 the rounding noise of float32 alone
+ *                exceeds an absolute threshold and it could never be met.  Each entry deflated by
+ *                it perturbs the eigenvalues by at most epsilon_abs, whatever ||A||: for ||A||_2
+ *                near 1 that is at the edge of the 1e-5 ||A||_2 accuracy bar, for small ||A|| it
+ *                is far outside.  0: the relative test alone (bed_syevd_info).  Finite and >= 0,
+ *                else BED_ERR_ARG.
  *   sweep_cap    > 0: at most this many QR sweeps per matrix (two per outer iteration; App. B runs
  *                n outer iterations, i.e. 2 n sweeps); off-diagonals still live then are counted in
  *                info.  0: the default cap of 30 n.  < 0: BED_ERR_ARG.

@@ -207,8 +207,8 @@ def bed_syevd_info(A, evals=None, evecs=None, *, want_vectors=True, stream=None,
 
 
 def bed_syevd_tol(A, epsilon_abs=0.0, sweep_cap=0, *, want_vectors=True, stream=None):
-    """bed_syevd_info with the paper's absolute deflation threshold (epsilon_abs > 0; App. B: 1e-5) and / or
-    a cap on the number of sweeps.  Returns (evals, evecs or None, info, rotations)."""
+    """bed_syevd_info with the paper's absolute deflation threshold (epsilon_abs > 0; App. B: 1e-5; an entry
+    is negligible if it passes that or the library's relative test) and / or a cap on the number of sweeps.  Returns (evals, evecs or None, info, rotations)."""
     import torch
     _check_dev(A, "A", torch.float32)
     batch, n = _square_batch(A)

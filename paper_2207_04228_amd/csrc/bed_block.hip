@@ -251,8 +251,7 @@ __global__ __launch_bounds__(BT) void block_kernel(KernelArgs args) {
     float d_lane[2];
     float2* const sP = sP_all + wv * BPA;
     PhaseClock clk;
-    const float paper_eps = args.abs_eps > 0.f ? args.abs_eps * pow2_reciprocal(inv_scale) : 0.f;
-    qr_iterations<BN, true, WANT_V, BLD>(sP, sV, lane, 32 * wv + (lane & 31), n, rotations, info, d_lane, args, paper_eps, clk);
+    qr_iterations<BN, true, WANT_V, BLD>(sP, sV, lane, 32 * wv + (lane & 31), n, rotations, info, d_lane, args, inv_scale, clk);
     __syncthreads();       // all four wavefronts leave after the same iteration; V is complete
 
     if (STAGE == kSpectral) {

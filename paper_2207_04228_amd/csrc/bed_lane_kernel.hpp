@@ -234,11 +234,10 @@ __global__ __launch_bounds__(64) void lane_kernel(KernelArgs args) {
         sweeps += (hi > lo) ? 1u : 0u;
     };
 
-    // args.abs_eps > 0: the paper's absolute test |e_k| <= epsilon (Sec. 3.2.3, App. B) instead of the
-    // relative one, in units of the pre-scaled matrix; no fallback then
-    const bool paper_mode = args.abs_eps > 0.f;
+    // absolute part of the deflation test: the rounding-level floor, or the paper's threshold
+    // epsilon (Sec. 3.2.3, App. B) in units of the pre-scaled matrix when the caller asked for it
     const float paper_eps = args.abs_eps * scale;
-    const float rel_tol = paper_mode ? 0.f : kEps;
+    const float tol0 = fmaxf(kTinyE, paper_eps), tol1 = fmaxf(2.3841858e-7f, paper_eps), tol2 = fmaxf(9.5367432e-7f, paper_eps);
     uint32_t live_prev = ~0u, stall = 0;      // iterations of this lane since its last deflation
     uint32_t relaxed = 0;                     // off-diagonals deflated only because the absolute fallback test accepted them
     while (true) {
@@ -246,12 +245,12 @@ __global__ __launch_bounds__(64) void lane_kernel(KernelArgs args) {
         // deflated anything for 12 (24) iterations also accepts entries below an absolute
         // threshold of 2^-22 (2^-20) of the pre-scaled matrix (at most 2e-6 ||A||_2 per entry;
         // counted and reported through info)
-        const float abs_tol = paper_mode ? paper_eps : (stall >= 24u ? 9.5367432e-7f : (stall >= 12u ? 2.3841858e-7f : kTinyE));
+        const float abs_tol = stall >= 24u ? tol2 : (stall >= 12u ? tol1 : tol0);
 #pragma unroll
         for (int k = 0; k < N - 1; ++k) {
             const float dsum = fabsf(d[k]) + fabsf(d[k + 1]);
-            const bool negl = fabsf(e[k]) <= fmaxf(rel_tol * dsum, abs_tol);
-            const bool base = paper_mode || fabsf(e[k]) <= fmaxf(kEps * dsum, kTinyE);
+            const bool negl = fabsf(e[k]) <= fmaxf(kEps * dsum, abs_tol);
+            const bool base = fabsf(e[k]) <= fmaxf(kEps * dsum, tol0);
             relaxed += ((live >> k) & 1u) && negl && !base ? 1u : 0u;
             live = negl ? (live & ~(1u << k)) : live;
         }

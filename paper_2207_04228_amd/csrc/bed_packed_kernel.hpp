@@ -348,16 +348,14 @@ __global__ __launch_bounds__(64) void packed_kernel(KernelArgs args) {
     uint32_t nz = 0, nz_prev = 0xFFFFFFFFu;
     bool live = r < n - 1;                 // off-diagonal e[r] is watched by this lane
     float dl = 0.f;
-    // args.abs_eps > 0: the paper's absolute test |e_k| <= epsilon (Sec. 3.2.3, App. B) instead of the
-    // relative one, in units of the pre-scaled matrix; no fallback then
-    const bool paper_mode = args.abs_eps > 0.f;
+    // absolute part of the deflation test: the rounding-level floor, or the paper's threshold
+    // epsilon (Sec. 3.2.3, App. B) in units of the pre-scaled matrix when the caller asked for it
     const float paper_eps = args.abs_eps * scale;
-    const float rel_tol = paper_mode ? 0.f : kEps;
+    const float tol0 = fmaxf(kTinyE, paper_eps), tol1 = fmaxf(kAbsTol1, paper_eps), tol2 = fmaxf(kAbsTol2, paper_eps);
     while (true) {
         // deflation test (Sec. 3.2.3, per matrix, every off-diagonal): the lane looks at e[r], d[r], d[r+1]
-        const bool widened = !paper_mode && stall >= kStallIterations;
-        const float abs_tol = paper_mode ? paper_eps
-                                         : (stall >= 2 * kStallIterations ? kAbsTol2 : (widened ? kAbsTol1 : kTinyE));
+        const bool widened = stall >= kStallIterations;
+        const float abs_tol = stall >= 2 * kStallIterations ? tol2 : (widened ? tol1 : tol0);
         float el = 0.f, dnext = 0.f;
         if (r < N) {
             const float2 pk = sP[r];
@@ -367,8 +365,8 @@ __global__ __launch_bounds__(64) void packed_kernel(KernelArgs args) {
             dnext = pk1.y;
         }
         const float dsum = fabsf(dl) + fabsf(dnext);
-        const bool negligible = fabsf(el) <= fmaxf(rel_tol * dsum, abs_tol);
-        const bool by_fallback = widened && live && negligible && !(fabsf(el) <= fmaxf(kEps * dsum, kTinyE));
+        const bool negligible = fabsf(el) <= fmaxf(kEps * dsum, abs_tol);
+        const bool by_fallback = widened && live && negligible && !(fabsf(el) <= fmaxf(kEps * dsum, tol0));
         relaxed += (uint32_t)__builtin_popcount(group_bits(__ballot(by_fallback)));
         live = live && !negligible;
         nz = group_bits(__ballot(live));

@@ -199,9 +199,8 @@ __global__ __launch_bounds__(256) void pair_kernel(KernelArgs args) {
     uint32_t rotations = 0;
     int info = 0;
     float d_lane[1];
-    const float paper_eps = args.abs_eps > 0.f ? args.abs_eps * pow2_reciprocal(sScale_all[pr]) : 0.f;
     qr_iterations<N, true, true, LD>(sP_all + wv * PA, sV, lane, 32 * (wv & 1) + (lane & 31), n, rotations, info, d_lane,
-                                     args, paper_eps, clk);
+                                     args, sScale_all[pr], clk);
     __syncthreads();       // both wavefronts of a pair leave after the same iteration; V is complete
 
     // ---- ascending order (wavefront A), then both wavefronts of the pair store ----

@@ -240,8 +240,8 @@ __device__ __forceinline__ void chain_finish(const Chain& S, float& e_out, float
 //          its own sweep.  Otherwise every lane owns a row and rotates it for both sweeps.
 // On return d_lane[bank] holds d[lane + 64 * bank].
 // ---------------------------------------------------------------------------
-template <int N, bool HALF, bool WANT_V, int LD>
-__device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV, const int lane, const int vrow,
+template <int N, bool HALF, bool WANT_V, int LD, bool PAPER_EPS>
+__device__ __forceinline__ void qr_iterations_impl(float2* const sP, float* const sV, const int lane, const int vrow,
                                               const int n, uint32_t& rotations, int& info,
                                               float (&d_lane)[(N + 63) / 64], const KernelArgs& args,
                                               const float paper_eps, PhaseClock& clk) {
@@ -262,8 +262,13 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
     for (int bk = 0; bk < NB; ++bk) nz_prev[bk] = ~0ull;
     uint32_t stall = 0;                 // iterations since the last deflation
     uint32_t relaxed = 0;               // off-diagonals deflated only because the absolute fallback test accepted them
-    const bool paper_mode = paper_eps > 0.f;
-    const float rel_tol = paper_mode ? 0.f : kEps;
+    // Absolute part of the deflation test: the rounding-level floor, or the paper's threshold
+    // epsilon (Sec. 3.2.3, App. B: 1e-5; here in units of the pre-scaled matrix) when the caller
+    // asked for it; the fallback thresholds of a stalled window never fall below it.
+    // Without a threshold from the caller (PAPER_EPS false) these are compile-time constants.
+    const float tol0 = PAPER_EPS ? fmaxf(kTinyE, paper_eps) : kTinyE;
+    const float tol1 = PAPER_EPS ? fmaxf(kAbsTol1, paper_eps) : kAbsTol1;
+    const float tol2 = PAPER_EPS ? fmaxf(kAbsTol2, paper_eps) : kAbsTol2;
     while (true) {
         // A window that has not deflated anything for kStallIterations iterations is stuck at the
         // rounding noise of the rotations, which is relative to the norm of the matrix and not to
@@ -273,11 +278,8 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
         // at least 0.5): dropping one perturbs the eigenvalues by at most 2e-6 ||A||_2, so every
         // matrix finishes within the accuracy bar instead of using up the sweep cap.  Entries
         // accepted only by that threshold are counted and reported through info.
-        // paper_eps > 0 selects the test of the paper as written instead: |e_k| <= epsilon, absolute
-        // (Sec. 3.2.3, App. B: 1e-5), here in units of the pre-scaled matrix; no fallback then.
-        const bool widened = !paper_mode && stall >= kStallIterations;
-        const float abs_tol = paper_mode ? paper_eps
-                                         : (stall >= 2 * kStallIterations ? kAbsTol2 : (widened ? kAbsTol1 : kTinyE));
+        const bool widened = stall >= kStallIterations;
+        const float abs_tol = stall >= 2 * kStallIterations ? tol2 : (widened ? tol1 : tol0);
         // deflation test, lane-parallel: the lane looks at e[k], d[k], d[k+1]
         float el[NB], dnext[NB];
         uint64_t any = 0;
@@ -295,10 +297,10 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
                 dnext[bk] = pk1.y;
             }
             const float dsum = fabsf(dl[bk]) + fabsf(dnext[bk]);
-            const bool negligible = fabsf(el[bk]) <= fmaxf(rel_tol * dsum, abs_tol);
+            const bool negligible = fabsf(el[bk]) <= fmaxf(kEps * dsum, abs_tol);
             if (widened)
                 relaxed += (uint32_t)__builtin_popcountll(
-                    __ballot(live[bk] && negligible && !(fabsf(el[bk]) <= fmaxf(kEps * dsum, kTinyE))));
+                    __ballot(live[bk] && negligible && !(fabsf(el[bk]) <= fmaxf(kEps * dsum, tol0))));
             live[bk] = live[bk] && !negligible;
             nz[bk] = __ballot(live[bk]);
             any |= nz[bk];
@@ -567,6 +569,20 @@ __device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV,
         d_lane[bk] = dl[bk];
     }
     info |= (int)(min(relaxed, 0x7FFFu) << 16);
+}
+
+// The two instantiations differ only in the thresholds above: the default path keeps them as
+// literals, so a caller that passes no threshold runs the same loop as before the option existed.
+template <int N, bool HALF, bool WANT_V, int LD>
+__device__ __forceinline__ void qr_iterations(float2* const sP, float* const sV, const int lane, const int vrow,
+                                              const int n, uint32_t& rotations, int& info,
+                                              float (&d_lane)[(N + 63) / 64], const KernelArgs& args,
+                                              const float inv_scale, PhaseClock& clk) {
+    if (args.abs_eps > 0.f)   // uniform over the grid
+        qr_iterations_impl<N, HALF, WANT_V, LD, true>(sP, sV, lane, vrow, n, rotations, info, d_lane, args,
+                                                       args.abs_eps * pow2_reciprocal(inv_scale), clk);
+    else
+        qr_iterations_impl<N, HALF, WANT_V, LD, false>(sP, sV, lane, vrow, n, rotations, info, d_lane, args, 0.f, clk);
 }
 
 // ---------------------------------------------------------------------------
@@ -848,8 +864,7 @@ __global__ __launch_bounds__(64) void wave_kernel(KernelArgs args) {
     } else {
         // ---- shifted QR iterations on the tridiagonal in sP ----
         float d_lane[1];
-        const float paper_eps = args.abs_eps > 0.f ? args.abs_eps * pow2_reciprocal(inv_scale) : 0.f;
-        qr_iterations<N, HALF, WANT_V, LD>(sP, sV, lane, row, n, rotations, info, d_lane, args, paper_eps, clk);
+        qr_iterations<N, HALF, WANT_V, LD>(sP, sV, lane, row, n, rotations, info, d_lane, args, inv_scale, clk);
         const float dl = d_lane[0];
         const int vrow = row;
         if (STAGE == kQrPartial) {

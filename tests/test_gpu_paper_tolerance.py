@@ -1,5 +1,5 @@
-"""bed_syevd_tol: the deflation test of the paper as written (absolute threshold epsilon on
-|e_k|, Sec. 3.2.3, App. B: 1e-5) and the sweep cap, in every kernel family.
+"""bed_syevd_tol: the paper's absolute threshold epsilon on |e_k| (Sec. 3.2.3, App. B: 1e-5),
+accepted beside the library's relative test, and the sweep cap, in every kernel family.
 
 What an absolute threshold guarantees (and what is asserted): every deflation sets to zero an
 off-diagonal of magnitude <= epsilon, a symmetric perturbation of 2-norm <= epsilon, so after at
@@ -77,6 +77,20 @@ def test_absolute_threshold_depends_on_the_scale_of_the_matrix():
     assert (err / norm2).max() > 1e-3                      # useless relative to ||A||_2 ...
     assert (np.abs(ev0 - lam_o).max(axis=1) / norm2).max() <= 1e-5   # ... where the relative test is unaffected
     assert rot.mean() < 0.5 * rot0.mean()
+
+
+def test_absolute_threshold_on_a_matrix_of_large_norm():
+    """||A||_2 near 1e3: the rounding noise of float32 (1e-7 ||A||) is above epsilon = 1e-5, so the absolute
+    test alone could never be met; the relative test beside it still ends every matrix within the bar."""
+    from oracle import jacobi
+    from paper_2207_04228_amd import workloads
+    for A0 in (workloads.config3(16, batch=128), workloads.config3(32, batch=32)):
+        A = (A0.astype(np.float64) * 1e3).astype(np.float32)
+        lam_o, _ = jacobi.syevd(A)
+        ev, V, info, rot = _run(A, EPS)
+        assert np.all(info == 0)
+        norm2 = np.abs(lam_o).max(axis=1)
+        assert np.all(np.abs(ev - lam_o).max(axis=1) <= 1e-5 * norm2)
 
 
 def test_zero_threshold_and_cap_reproduce_bed_syevd_info():
