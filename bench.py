@@ -8,9 +8,9 @@ four `bed_syevd` calls, batch 512 each, n = 4, 8, 16, 32 (2048 matrices),
 inputs already resident in HBM.  The script prints ONE JSON line:
 
   value        matrices/s over the K timed steps (wall clock, synchronised)
-  per_n        per-call figures for each n (HIP events around every call; the
-               dominant call, n = 32, is measured inside the timed region, the
-               others in a second pass so that their events do not sit in it)
+  per_n        per-call figures for each n (every kernel launched with a start and a stop
+               HIP event of its own on the launch stream; the dominant call, n = 32, is
+               measured inside the timed region, the others in a second pass)
   roofline     the dominant kernel (n = 32): algorithmic flops / mean launch
                duration against the fp32 vector peak (datasheet, packed), the plain-FMA
                peak, and ceilings measured in this run (plain-FMA kernel, device copy)
@@ -225,20 +225,19 @@ def main(argv=None) -> int:
         step()
     torch.cuda.synchronize()
 
-    # ---- timed region: K steps; HIP events (on the launch stream) around the dominant call ----
+    # ---- timed region: K steps; the dominant call (n = 32) is launched with a start and a stop
+    # event of its own (bed_timing_*: the dispatch's begin and end timestamps on the launch
+    # stream, no marker packets between the kernels) ----
     dom_i = len(bufs) - 1                      # n = 32
-    starts = [torch.cuda.Event(enable_timing=True) for _ in range(a.steps)]
-    stops = [torch.cuda.Event(enable_timing=True) for _ in range(a.steps)]
-    for e_ in starts + stops:                  # first use creates the HIP event: keep that out of the timing
-        e_.record(stream)
+    binding.bed_timing_begin(a.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(a.steps):
         for i, (n, A, ev, V) in enumerate(bufs):
             if i == dom_i:
-                starts[k].record(stream)
+                binding.bed_timing_arm(True)
                 binding.bed_syevd(A, ev, V)
-                stops[k].record(stream)
+                binding.bed_timing_arm(False)
             else:
                 binding.bed_syevd(A, ev, V)
     torch.cuda.synchronize()
@@ -246,26 +245,22 @@ def main(argv=None) -> int:
     wall = t1 - t0
     n_mats = sum(int(A.shape[0]) for _, A, _, _ in bufs)
     value = n_mats * a.steps / wall
-    dom_durs = np.array([starts[k].elapsed_time(stops[k]) for k in range(a.steps)]) * 1e-3  # s
+    dom_us, timed = binding.bed_timing_end(a.steps)
+    assert timed == a.steps, (timed, a.steps)
+    dom_durs = dom_us.astype(np.float64) * 1e-6   # s
 
-    # ---- per-n figures: a second, untimed pass with events around every call ----
-    ev_a = [[torch.cuda.Event(enable_timing=True) for _ in bufs] for _ in range(a.steps)]
-    ev_b = [[torch.cuda.Event(enable_timing=True) for _ in bufs] for _ in range(a.steps)]
-    for row in ev_a + ev_b:
-        for e_ in row:
-            e_.record(stream)
-    torch.cuda.synchronize()
-    step()                                     # keep the queue non-empty: on an idle queue the first start
-    step()                                     # event is processed before the host has submitted its kernel
+    # ---- per-n figures: a second, untimed pass with every call timed the same way ----
+    binding.bed_timing_begin(a.steps * len(bufs))
+    binding.bed_timing_arm(True)
     for k in range(a.steps):
-        for i, (n, A, ev, V) in enumerate(bufs):
-            ev_a[k][i].record(stream)
-            binding.bed_syevd(A, ev, V)
-            ev_b[k][i].record(stream)
+        step()
     torch.cuda.synchronize()
+    all_us, timed = binding.bed_timing_end(a.steps * len(bufs))
+    assert timed == a.steps * len(bufs), timed
+    all_durs = all_us.astype(np.float64).reshape(a.steps, len(bufs)) * 1e-6
     per_n = {}
     for i, (n, A, ev, V) in enumerate(bufs):
-        durs = np.array([ev_a[k][i].elapsed_time(ev_b[k][i]) for k in range(a.steps)]) * 1e-3  # s
+        durs = all_durs[:, i]
         if i == dom_i:
             durs = dom_durs                    # the dominant kernel: measured inside the timed region
         mean = float(durs.mean())

@@ -332,6 +332,29 @@ int bed_ceiling_fma(float* out, int blocks, int threads, int chains, int iters, 
 int bed_ceiling_copy(const float* src, float* dst, size_t count, int blocks, void* stream);
 
 /*
+ * Measurement aid: the duration of the library's own kernels, one figure per launch, taken from
+ * the dispatch's begin and end timestamps (each timed kernel is launched with a start and a stop
+ * event of its own; no marker is queued between the kernels of the stream, which a pair of
+ * events recorded around a call would add, at 2-3 us per pair).  State is per host thread.
+ *   bed_timing_begin(capacity)  creates 2 * capacity events (host side; 1 <= capacity <= 2^20)
+ *                               for the calling thread, not yet armed; BED_ERR_LAUNCH if the
+ *                               runtime refuses, BED_ERR_ARG for a capacity out of range.
+ *   bed_timing_arm(on)          on != 0: from now on every kernel that this thread launches
+ *                               through the library is timed, until `capacity` launches have been
+ *                               timed (later ones run untimed); 0: launches run untimed again.
+ *                               BED_ERR_ARG without a bed_timing_begin.
+ *   bed_timing_end(us, max_count, count)
+ *                               waits for the timed kernels, writes their durations in
+ *                               microseconds, in launch order, to us[0 .. min(*count, max_count))
+ *                               (host memory), sets *count to the number of timed launches and
+ *                               destroys the events.  BED_ERR_ARG without a bed_timing_begin or
+ *                               for null pointers, BED_ERR_LAUNCH if an event could not be read.
+ */
+int bed_timing_begin(int capacity);
+int bed_timing_arm(int on);
+int bed_timing_end(float* microseconds, int max_count, int* count);
+
+/*
  * Name of the kernel that bed_syevd (want_vectors = 1) or its eigenvalues-only form
  * (want_vectors = 0) launches for this batch and n, e.g. "wave_kernel<32>" (one wavefront per
  * matrix, register arrays of 32), "packed_kernel<16>" (several matrices per wavefront),

@@ -17,6 +17,9 @@ from .binding import (  # noqa: F401
     BED_FN_SQRT,
     BedError,
     bed_ceiling_copy,
+    bed_timing_begin,
+    bed_timing_arm,
+    bed_timing_end,
     bed_ceiling_fma,
     bed_kernel_variant,
     bed_spd_fn,

@@ -72,6 +72,12 @@ def load_library():
         lib.bed_ceiling_fma.restype = ci
         lib.bed_ceiling_copy.argtypes = [vp, vp, ctypes.c_size_t, ci, vp]
         lib.bed_ceiling_copy.restype = ci
+        lib.bed_timing_begin.argtypes = [ci]
+        lib.bed_timing_begin.restype = ci
+        lib.bed_timing_arm.argtypes = [ci]
+        lib.bed_timing_arm.restype = ci
+        lib.bed_timing_end.argtypes = [vp, ci, vp]
+        lib.bed_timing_end.restype = ci
         lib.bed_kernel_variant.argtypes = [ci, ci, ci]
         lib.bed_kernel_variant.restype = ctypes.c_char_p
         lib.bed_status_string.argtypes = [ci]
@@ -110,6 +116,32 @@ def bed_ceiling_copy(src, dst, blocks, *, stream=None):
     if st != 0:
         raise BedError(st, "bed_ceiling_copy")
     return 8.0 * src.numel()
+
+
+def bed_timing_begin(capacity: int) -> None:
+    """Measurement aid: prepares per-launch timing of up to `capacity` of this thread's launches."""
+    st = load_library().bed_timing_begin(int(capacity))
+    if st != 0:
+        raise BedError(st, "bed_timing_begin")
+
+
+def bed_timing_arm(on: bool) -> None:
+    """Measurement aid: from now on this thread's launches are (on) / are not (off) timed."""
+    st = load_library().bed_timing_arm(1 if on else 0)
+    if st != 0:
+        raise BedError(st, "bed_timing_arm")
+
+
+def bed_timing_end(max_count: int):
+    """Measurement aid: waits for the timed kernels and returns their durations in microseconds
+    (numpy float32, launch order; at most max_count of them) and the number of timed launches."""
+    import numpy as np
+    us = np.zeros((max(int(max_count), 1),), dtype=np.float32)
+    count = ctypes.c_int(0)
+    st = load_library().bed_timing_end(us.ctypes.data_as(ctypes.c_void_p), int(max_count), ctypes.byref(count))
+    if st != 0:
+        raise BedError(st, "bed_timing_end")
+    return us[:min(count.value, int(max_count))].copy(), count.value
 
 
 def bed_version() -> int:

@@ -2,10 +2,27 @@
 #ifndef BED_KERNEL_H
 #define BED_KERNEL_H
 
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 namespace bed {
+
+// Per-launch kernel timing (bed_timing_* of the C ABI): while a thread has armed its timer, each
+// kernel it enqueues through this library is launched with a start and a stop event of its own
+// (hipExtLaunchKernel: the events take the dispatch's own begin and end timestamps, with no marker
+// packets between the kernels of the stream).
+struct LaunchTimer {
+    hipEvent_t* start = nullptr;
+    hipEvent_t* stop = nullptr;
+    int capacity = 0;
+    int used = 0;
+    bool armed = false;
+};
+inline LaunchTimer& launch_timer() {
+    static thread_local LaunchTimer timer;
+    return timer;
+}
 
 // Launches `kernel` and returns the status of THIS launch.  (Reading hipGetLastError() after a
 // triple-chevron launch would also report, and consume, an error left behind by an unrelated
@@ -17,6 +34,12 @@ template <typename... KArgs>
 inline hipError_t enqueue(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t stream,
                           typename same_type<KArgs>::type... args) {
     void* argv[] = {const_cast<void*>(static_cast<const void*>(&args))...};
+    LaunchTimer& t = launch_timer();
+    if (t.armed && t.used < t.capacity) {
+        const int i = t.used++;
+        return hipExtLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, argv, 0, stream, t.start[i],
+                                  t.stop[i], 0);
+    }
     return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, argv, 0, stream);
 }
 

@@ -34,6 +34,17 @@ def test_header_symbols_are_exported(lib):
         assert hasattr(lib, name), name
 
 
+def test_timing_calls_without_a_timer_are_refused(lib):
+    """The per-launch timing aid keeps its state per thread; nothing here touches a GPU."""
+    assert lib.bed_timing_begin(0) == -7
+    assert lib.bed_timing_begin(-3) == -7
+    assert lib.bed_timing_begin((1 << 20) + 1) == -7
+    assert lib.bed_timing_arm(1) == -7                          # no bed_timing_begin before it
+    cnt = ctypes.c_int(-1)
+    assert lib.bed_timing_end(None, 0, ctypes.byref(cnt)) == -7
+    assert cnt.value == -1
+
+
 def test_version_and_status_strings(lib):
     assert binding.bed_version() == 500
     assert binding.bed_status_string(0) == "BED_OK"
