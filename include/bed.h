@@ -336,6 +336,7 @@ int bed_ceiling_copy(const float* src, float* dst, size_t count, int blocks, voi
  * the dispatch's begin and end timestamps (each timed kernel is launched with a start and a stop
  * event of its own; no marker is queued between the kernels of the stream, which a pair of
  * events recorded around a call would add, at 2-3 us per pair).  State is per host thread.
+ * Not for launches into a stream that is being captured into a graph: disarm first.
  *   bed_timing_begin(capacity)  creates 2 * capacity events (host side; 1 <= capacity <= 2^20)
  *                               for the calling thread, not yet armed; BED_ERR_LAUNCH if the
  *                               runtime refuses, BED_ERR_ARG for a capacity out of range.

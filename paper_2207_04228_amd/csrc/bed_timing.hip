@@ -1,5 +1,5 @@
 // Kernel-level timing of the library's own launches (measurement aid of the benchmark).
-#include "../../include/bed.h"
+#include "bed.h"
 #include "bed_kernel.h"
 
 namespace {
