@@ -134,6 +134,8 @@ int bed_syevd_tol(const float* A, int batch, int n, float* evals, float* evecs, 
  *   BED_FAMILY_BLOCK   four wavefronts per matrix, 64 < n <= 128
  *   BED_FAMILY_PAIR    two wavefronts per matrix, 32 < n <= 64, eigenvectors required
  *                      (BED_ERR_NULL without evecs)
+ *   BED_FAMILY_PACKED_ROWS  four matrices per wavefront, 16 lanes each with two rows per lane,
+ *                      n <= 32 (meant for 16 < n <= 32)
  * BED_ERR_N if the family does not serve this n, BED_ERR_ARG for an unknown family.
  */
 typedef enum {
@@ -142,7 +144,8 @@ typedef enum {
     BED_FAMILY_PACKED = 2,
     BED_FAMILY_LANE = 3,
     BED_FAMILY_BLOCK = 4,
-    BED_FAMILY_PAIR = 5
+    BED_FAMILY_PAIR = 5,
+    BED_FAMILY_PACKED_ROWS = 6
 } bed_family;
 int bed_syevd_family(const float* A, int batch, int n, float* evals, float* evecs, int* info,
                      unsigned* rotations, int family, void* stream);

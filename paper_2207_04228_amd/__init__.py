@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     BED_FAMILY_LANE,
     BED_FAMILY_PACKED,
     BED_FAMILY_PAIR,
+    BED_FAMILY_PACKED_ROWS,
     BED_FAMILY_WAVE,
     BED_FN_INV_SQRT,
     BED_GRAD_EXACT,

@@ -211,7 +211,7 @@ def bed_syevd(A, evals=None, evecs=None, *, want_vectors=True, stream=None):
     return evals, evecs
 
 
-BED_FAMILY_AUTO, BED_FAMILY_WAVE, BED_FAMILY_PACKED, BED_FAMILY_LANE, BED_FAMILY_BLOCK, BED_FAMILY_PAIR = range(6)
+BED_FAMILY_AUTO, BED_FAMILY_WAVE, BED_FAMILY_PACKED, BED_FAMILY_LANE, BED_FAMILY_BLOCK, BED_FAMILY_PAIR, BED_FAMILY_PACKED_ROWS = range(7)
 
 
 def bed_syevd_info(A, evals=None, evecs=None, *, want_vectors=True, stream=None, family=BED_FAMILY_AUTO):

@@ -112,7 +112,7 @@ int syevd_checked(const float* A, int batch, int n, float* evals, float* evecs, 
                   int family, float epsilon_abs, int sweep_cap, void* stream) {
     int st = check_common(batch, n);
     if (st != BED_OK) return st;
-    if (family < BED_FAMILY_AUTO || family > BED_FAMILY_PAIR) return BED_ERR_ARG;
+    if (family < BED_FAMILY_AUTO || family > BED_FAMILY_PACKED_ROWS) return BED_ERR_ARG;
     if (family == BED_FAMILY_PAIR && !evecs) return BED_ERR_NULL;
     if (!bed::family_serves(family, n)) return BED_ERR_N;
     if (batch == 0) return BED_OK;

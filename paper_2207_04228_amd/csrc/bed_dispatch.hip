@@ -6,6 +6,7 @@ namespace bed {
 hipError_t launch_lane(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_packed(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_pair(const KernelArgs&, hipStream_t);
+hipError_t launch_packed_rows(const KernelArgs&, bool, hipStream_t);
 hipError_t launch_wave_n4(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n8(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n12(const KernelArgs&, int, bool, hipStream_t);
@@ -24,11 +25,13 @@ namespace {
 
 constexpr int kPackedFromBatch = 2560;
 constexpr int kPacked32FromBatch = 4096;
+constexpr int kPackedRowsFromBatch = 4096;
+constexpr int kPackedRowsValuesFromBatch = 3072;   // eigenvalues only
 constexpr int kPairUpToBatch = 512;
 constexpr int kLane4FromBatch = 20480;
 constexpr int kLane8FromBatch = 32768;
 
-enum Family { kLaneFamily, kPackedFamily, kWaveFamily, kPairFamily, kBlockFamily };
+enum Family { kLaneFamily, kPackedFamily, kWaveFamily, kPairFamily, kBlockFamily, kPackedRowsFamily };
 struct Choice {
     Family family;
     int N;               // register-array size of the instantiation (0 for the block kernel)
@@ -52,6 +55,12 @@ Choice choose(int batch, int n, int stage, bool want_v, int forced) {
     if (forced == kFamilyWave) return wave_choice(n);
     if (forced == kFamilyPair) return {kPairFamily, 0, n <= 40 ? "pair_kernel<40>" : n <= 48 ? "pair_kernel<48>" : n <= 56 ? "pair_kernel<56>" : "pair_kernel<64>"};
     if (forced == kFamilyBlock) return {kBlockFamily, 0, "block_kernel"};
+    if (forced == kFamilyPackedRows) {
+        if (n <= 20) return {kPackedRowsFamily, 20, "packed_rows_kernel<20>"};
+        if (n <= 24) return {kPackedRowsFamily, 24, "packed_rows_kernel<24>"};
+        if (n <= 28) return {kPackedRowsFamily, 28, "packed_rows_kernel<28>"};
+        return {kPackedRowsFamily, 32, "packed_rows_kernel<32>"};
+    }
     // Measured crossovers on MI355X (us per launch, eigenvectors on; wave / packed / lane):
     //   n = 4:  batch 2048: 8.4 / 8.6 / 13.0   4096: 11.5 / 9.1 / 13.7   16384: 27.7 / 13.2 / 14.2   32768: 49 / 21.7 / 14.9
     //   n = 8:  batch 2048: 17.2 / 17.8 / 49.5  4096: 25.3 / 18.0 / 49.4  32768: 127 / 58.1 / 56.6    65536: 231 / 96.9 / 57.6
@@ -68,8 +77,18 @@ Choice choose(int batch, int n, int stage, bool want_v, int forced) {
     if (whole && n <= 4 && batch >= kLane4FromBatch) return {kLaneFamily, 4, "lane_kernel<4>"};
     if (whole && n <= 8 && batch >= kLane8FromBatch) return {kLaneFamily, 8, "lane_kernel<8>"};
     if (whole && n <= 16 && batch >= kPackedFromBatch) return choose(batch, n, stage, want_v, kFamilyPacked);
-    // two matrices per wavefront for 16 < n <= 32: a smaller gain (the one-wavefront kernel already
-    // serves both sweeps of such a matrix with one instruction stream), from a larger batch
+    // 16 < n <= 32, from batch 4096 (us per launch, wave / two per wavefront / four per wavefront with
+    // two rows per lane:
+    //   n = 20: batch 3072: 72.8 / 80.5 / 75.3   4096: 87.5 / 80.6 / 74.7   8192: 146 / 124 / 97    16384: 264 / 220 / 195
+    //   n = 24: batch 3072: 93.6 / 97.5 / 96.3   4096: 115 / 101 / 95       8192: 193 / 163 / 129   16384: 355 / 288 / 238
+    //   n = 28: batch 3072: 119 / 130 / 125      4096: 145 / 131 / 124      8192: 247 / 232 / 165   16384: 456 / 400 / 309
+    //   n = 32: batch 3072: 148 / 162 / 152      4096: 180 / 163 / 152      8192: 309 / 275 / 205   16384: 571 / 488 / 379):
+    // the whole decomposition takes four matrices per wavefront; the fused spectral function, which
+    // that kernel does not have, two (the one-wavefront kernel already serves both sweeps of such a
+    // matrix with one instruction stream, so the gain of sharing is smaller than for n <= 16)
+    // (eigenvalues only, n = 32: batch 3072: 125 / 109 / 95   4096: 149 / 108 / 94   16384: 479 / 379 / 230)
+    if (stage == kFull && n > 16 && n <= 32 && batch >= (want_v ? kPackedRowsFromBatch : kPackedRowsValuesFromBatch))
+        return choose(batch, n, stage, want_v, kFamilyPackedRows);
     if (whole && n <= 32 && batch >= kPacked32FromBatch) return choose(batch, n, stage, want_v, kFamilyPacked);
     // 32 < n <= 64 with eigenvectors while the chip is mostly idle: two wavefronts per matrix
     // (us per launch, wave / pair: n = 48: batch 256: 175 / 165, 512: 179 / 168, 768: 179 / 203;
@@ -106,6 +125,7 @@ bool family_serves(int family, int n) {
         case kFamilyLane: return n >= 1 && n <= 8;
         case kFamilyBlock: return n > 64 && n <= 128;
         case kFamilyPair: return n > 32 && n <= 64;
+        case kFamilyPackedRows: return n >= 1 && n <= 32;
         default: return false;
     }
 }
@@ -116,6 +136,10 @@ hipError_t launch(const KernelArgs& args, int stage, bool want_v, hipStream_t st
     if (c.family == kPairFamily) {
         if (!want_v || stage != kFull) return hipErrorInvalidValue;     // the pair kernels always form eigenvectors
         return launch_pair(args, stream);
+    }
+    if (c.family == kPackedRowsFamily) {
+        if (stage != kFull) return hipErrorInvalidValue;     // whole path only
+        return launch_packed_rows(args, want_v, stream);
     }
     if (c.family == kLaneFamily) return launch_lane(args, stage, want_v, stream);
     if (c.family == kPackedFamily) return launch_packed(args, stage, want_v, stream);

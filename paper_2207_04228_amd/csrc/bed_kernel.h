@@ -140,7 +140,7 @@ hipError_t lockstep_scratch(void** ptr);
 const char* kernel_variant(int batch, int n, bool want_v);
 
 // Kernel families (values of bed_family in bed.h).
-enum FamilyId { kFamilyAuto = 0, kFamilyWave = 1, kFamilyPacked = 2, kFamilyLane = 3, kFamilyBlock = 4, kFamilyPair = 5 };
+enum FamilyId { kFamilyAuto = 0, kFamilyWave = 1, kFamilyPacked = 2, kFamilyLane = 3, kFamilyBlock = 4, kFamilyPair = 5, kFamilyPackedRows = 6 };
 bool family_serves(int family, int n);
 
 // Enqueue one launch; returns the status of that launch.  `forced`: a family other than

@@ -1,0 +1,9 @@
+// Four matrices per wavefront, two rows per lane (instantiations for 24 < n <= 32).
+#include "bed_packed_rows_kernel.hpp"
+
+namespace bed {
+hipError_t launch_packed_rows_32(const KernelArgs& args, bool want_v, hipStream_t stream) {
+    if (args.n <= 28) return launch_packed_rows_n<28>(args, want_v, stream);
+    return launch_packed_rows_n<32>(args, want_v, stream);
+}
+}  // namespace bed

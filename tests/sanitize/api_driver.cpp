@@ -71,7 +71,7 @@ int main() {
     EXPECT(bed_syevd_family(A, 8, 16, L, V, I, R, BED_FAMILY_PACKED, nullptr), BED_OK);
     EXPECT(bed_syevd_family(A, 8, 33, L, V, I, R, BED_FAMILY_PACKED, nullptr), BED_ERR_N);
     EXPECT(bed_syevd_family(A, 8, 9, L, V, I, R, BED_FAMILY_LANE, nullptr), BED_ERR_N);
-    EXPECT(bed_syevd_family(A, 8, 16, L, V, I, R, 6, nullptr), BED_ERR_ARG);
+    EXPECT(bed_syevd_family(A, 8, 16, L, V, I, R, 7, nullptr), BED_ERR_ARG);
     EXPECT(bed_syevd_family(A, 8, 48, L, nullptr, I, R, BED_FAMILY_PAIR, nullptr), BED_ERR_NULL);
     EXPECT(bed_syevd_family(A, 8, 48, L, V, I, R, BED_FAMILY_PAIR, nullptr), BED_OK);
     EXPECT(bed_syevd_family(A, 8, 16, L, V, I, R, -1, nullptr), BED_ERR_ARG);

@@ -9,8 +9,8 @@ int g_stub_launches = 0;
 namespace bed {
 hipError_t launch(const KernelArgs&, int, bool, hipStream_t, int) { ++g_stub_launches; return hipSuccess; }
 bool family_serves(int family, int n) {        // the real table lives beside the kernels
-    const int limit[] = {128, 64, 32, 8, 128, 64};
-    return family >= 0 && family <= 5 && n >= 1 && n <= limit[family];
+    const int limit[] = {128, 64, 32, 8, 128, 64, 32};
+    return family >= 0 && family <= 6 && n >= 1 && n <= limit[family];
 }
 hipError_t launch_grad(const GradArgs&, hipStream_t) { ++g_stub_launches; return hipSuccess; }
 hipError_t launch_lockstep(const LockstepArgs&, hipStream_t) { ++g_stub_launches; return hipSuccess; }

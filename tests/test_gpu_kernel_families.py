@@ -42,6 +42,7 @@ def _check(A32, family, name, allow_fallback=False):
 PACKED = 2
 LANE = 3
 WAVE = 1
+PACKED_ROWS = 6
 
 
 @pytest.mark.parametrize("n", list(range(1, 33)))
@@ -108,6 +109,66 @@ def test_packed_kernel_structured_and_repeated():
             _check(workloads.from_spectrum(lam, seed=kind + n), PACKED, f"packed_repeated_n{n}_{kind}")
 
 
+@pytest.mark.parametrize("n", list(range(1, 33)))
+def test_packed_rows_kernel_every_n(n):
+    """Four matrices per wavefront with two rows per lane, every n it accepts (it is dispatched for
+    16 < n <= 32); batches that leave groups of the last wavefront empty; indefinite input."""
+    rng = np.random.default_rng(8600 + n)
+    for batch in (1, 2, 3, 4, 5, 37, 258):
+        A = rng.standard_normal((batch, n, n))
+        A = (0.5 * (A + A.transpose(0, 2, 1))).astype(np.float32)
+        _check(A, PACKED_ROWS, f"packed_rows_n{n}_b{batch}")
+
+
+def test_packed_rows_kernel_on_the_configs_and_where_it_is_dispatched():
+    from paper_2207_04228_amd import binding, workloads
+    _check(workloads.config3(24), PACKED_ROWS, "packed_rows_config3_n24")
+    _check(workloads.config3(32), PACKED_ROWS, "packed_rows_config3_n32")
+    for n in (20, 24, 28, 32):
+        assert binding.bed_kernel_variant(4096, n) == f"packed_rows_kernel<{n}>"
+        assert binding.bed_kernel_variant(4096, n, False) == f"packed_rows_kernel<{n}>"
+        assert binding.bed_kernel_variant(4095, n) == f"wave_kernel<{n}>"
+        assert binding.bed_kernel_variant(3072, n, False) == f"packed_rows_kernel<{n}>"
+        assert binding.bed_kernel_variant(3071, n, False) == f"wave_kernel<{n}>"
+    assert binding.bed_kernel_variant(4096, 17) == "packed_rows_kernel<20>"
+    assert binding.bed_kernel_variant(4096, 16) == "packed_kernel<16>"
+    # through the automatic dispatch, ragged last wavefront
+    A = workloads.config3(32, batch=4099)
+    _check(A, 0, "auto_n32_b4099")
+    _check(workloads.config3(21, batch=4097), 0, "auto_n21_b4097")
+
+
+def test_packed_rows_kernel_mixed_convergence_nan_and_structure():
+    from paper_2207_04228_amd import workloads
+    n = 28
+    rng = np.random.default_rng(8700)
+    dense = rng.standard_normal((8, n, n))
+    dense = 0.5 * (dense + dense.transpose(0, 2, 1))
+    rep = workloads.from_spectrum(np.round(rng.uniform(0, 2, (8, n))), seed=6).astype(np.float64)
+    mats = [np.diag(np.arange(n, 0, -1.0)), np.zeros((n, n)), np.eye(n), dense[0], rep[0], dense[1], np.eye(n) * -3,
+            rep[1], 2.0 * np.eye(n) - np.eye(n, k=1) - np.eye(n, k=-1), dense[2], rep[2], np.zeros((n, n)), dense[3]]
+    A = np.stack(mats).astype(np.float32)
+    lam, V, rot = _check(A, PACKED_ROWS, "packed_rows_mixed")
+    assert np.array_equal(lam[0], np.arange(1, n + 1, dtype=np.float32))
+    assert np.array_equal(lam[1], np.zeros(n, dtype=np.float32))
+    assert np.array_equal(lam[2], np.ones(n, dtype=np.float32))
+    assert rot[1] == 0 and rot[2] == 0
+    B = workloads.config3(24, batch=10).copy()
+    B[5, 20, 1] = np.nan
+    B[6, 0, 0] = np.inf
+    lam, V, info, rot = _solve(B, PACKED_ROWS)
+    good = [0, 1, 2, 3, 4, 7, 8, 9]
+    assert np.isfinite(lam[good]).all() and np.isfinite(V[good]).all() and np.all(info[good] == 0)
+    assert info[5] > 0 and info[6] > 0 and not np.isfinite(lam[5]).all()
+    for m in (21, 32):
+        for name, S in workloads.structured_cases(m, 16, seed=950 + m):
+            _check(S, PACKED_ROWS, f"packed_rows_structured_n{m}_{name}", allow_fallback=True)
+        r2 = np.random.default_rng(8800 + m)
+        for kind, sp in enumerate((np.round(r2.uniform(0, 3, (48, m))),
+                                   np.where(r2.uniform(0, 1, (48, m)) < 0.5, 1.0, 1.0 + 1e-6))):
+            _check(workloads.from_spectrum(sp, seed=kind + m), PACKED_ROWS, f"packed_rows_repeated_n{m}_{kind}")
+
+
 @pytest.mark.parametrize("n,batch", [(4, 64), (4, 1000), (8, 130), (6, 513)])
 def test_lane_kernel_at_small_batches(n, batch):
     rng = np.random.default_rng(8400 + n)
@@ -127,7 +188,7 @@ def test_family_argument_checks():
     import torch
     from paper_2207_04228_amd import binding
     A = torch.zeros((4, 33, 33), dtype=torch.float32, device="cuda:0")
-    for fam in (PACKED, LANE, 4):
+    for fam in (PACKED, LANE, 4, PACKED_ROWS):
         with pytest.raises(binding.BedError) as e:
             binding.bed_syevd_info(A, family=fam)
         assert e.value.status == -3

@@ -28,7 +28,7 @@ def _cases():
     return [("wave_kernel<16>", workloads.config3(16)),
             ("wave_kernel<32>", workloads.config3(32, batch=64)),
             ("packed_kernel<16>", workloads.config4()),
-            ("packed_kernel<24>", workloads.config3(24, batch=4096)),
+            ("packed_rows_kernel<24>", workloads.config3(24, batch=4096)),
             ("lane_kernel<4>", workloads.config2(65536)[:20480 + 7]),
             ("pair_kernel<48>", workloads.config5(48, batch=32)),
             ("block_kernel", workloads.covariance(6, 100, 400, 1e-4, 77))]

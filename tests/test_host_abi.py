@@ -93,8 +93,8 @@ def test_argument_validation_is_host_side(lib):
     assert binding.bed_kernel_variant(4096, 4) == "packed_kernel<4>"
     assert binding.bed_kernel_variant(2048, 16) == "wave_kernel<16>"
     assert binding.bed_kernel_variant(4095, 17) == "wave_kernel<20>"
-    assert binding.bed_kernel_variant(4096, 17) == "packed_kernel<24>"
-    assert binding.bed_kernel_variant(4096, 32) == "packed_kernel<32>"
+    assert binding.bed_kernel_variant(4096, 17) == "packed_rows_kernel<20>"
+    assert binding.bed_kernel_variant(4096, 32) == "packed_rows_kernel<32>"
     assert binding.bed_kernel_variant(4096, 33) == "wave_kernel<40>"
     assert binding.bed_kernel_variant(256, 100) == "block_kernel"
     assert binding.bed_kernel_variant(256, 64) == "pair_kernel<64>"
