@@ -6,7 +6,7 @@ namespace bed {
 hipError_t launch_lane(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_packed(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_pair(const KernelArgs&, hipStream_t);
-hipError_t launch_packed_rows(const KernelArgs&, bool, hipStream_t);
+hipError_t launch_packed_rows(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n4(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n8(const KernelArgs&, int, bool, hipStream_t);
 hipError_t launch_wave_n12(const KernelArgs&, int, bool, hipStream_t);
@@ -24,7 +24,6 @@ hipError_t launch_block(const KernelArgs&, int, bool, hipStream_t);
 namespace {
 
 constexpr int kPackedFromBatch = 2560;
-constexpr int kPacked32FromBatch = 4096;
 constexpr int kPackedRowsFromBatch = 4096;
 constexpr int kPackedRowsValuesFromBatch = 3072;   // eigenvalues only
 constexpr int kPairUpToBatch = 512;
@@ -83,13 +82,11 @@ Choice choose(int batch, int n, int stage, bool want_v, int forced) {
     //   n = 24: batch 3072: 93.6 / 97.5 / 96.3   4096: 115 / 101 / 95       8192: 193 / 163 / 129   16384: 355 / 288 / 238
     //   n = 28: batch 3072: 119 / 130 / 125      4096: 145 / 131 / 124      8192: 247 / 232 / 165   16384: 456 / 400 / 309
     //   n = 32: batch 3072: 148 / 162 / 152      4096: 180 / 163 / 152      8192: 309 / 275 / 205   16384: 571 / 488 / 379):
-    // the whole decomposition takes four matrices per wavefront; the fused spectral function, which
-    // that kernel does not have, two (the one-wavefront kernel already serves both sweeps of such a
-    // matrix with one instruction stream, so the gain of sharing is smaller than for n <= 16)
+    // four matrices per wavefront, also for the fused spectral function (16384 x 32x32: 529 us with
+    // two per wavefront, 388 us with four); two per wavefront remains for forced-family runs
     // (eigenvalues only, n = 32: batch 3072: 125 / 109 / 95   4096: 149 / 108 / 94   16384: 479 / 379 / 230)
-    if (stage == kFull && n > 16 && n <= 32 && batch >= (want_v ? kPackedRowsFromBatch : kPackedRowsValuesFromBatch))
+    if (whole && n > 16 && n <= 32 && batch >= (want_v ? kPackedRowsFromBatch : kPackedRowsValuesFromBatch))
         return choose(batch, n, stage, want_v, kFamilyPackedRows);
-    if (whole && n <= 32 && batch >= kPacked32FromBatch) return choose(batch, n, stage, want_v, kFamilyPacked);
     // 32 < n <= 64 with eigenvectors while the chip is mostly idle: two wavefronts per matrix
     // (us per launch, wave / pair: n = 48: batch 256: 175 / 165, 512: 179 / 168, 768: 179 / 203;
     //  n = 64: batch 256: 285 / 274, 512: 293 / 274, 768: 290 / 327)
@@ -138,8 +135,8 @@ hipError_t launch(const KernelArgs& args, int stage, bool want_v, hipStream_t st
         return launch_pair(args, stream);
     }
     if (c.family == kPackedRowsFamily) {
-        if (stage != kFull) return hipErrorInvalidValue;     // whole path only
-        return launch_packed_rows(args, want_v, stream);
+        if (stage != kFull && stage != kSpectral) return hipErrorInvalidValue;     // no stage hooks
+        return launch_packed_rows(args, stage, want_v, stream);
     }
     if (c.family == kLaneFamily) return launch_lane(args, stage, want_v, stream);
     if (c.family == kPackedFamily) return launch_packed(args, stage, want_v, stream);

@@ -15,9 +15,11 @@
 namespace bed {
 
 // N: register-array size (20, 24, 28, 32), 16 < n <= N at run time (smaller n work, wastefully).
-// Whole path only (STAGE kFull), with or without eigenvectors.
-template <int N, bool WANT_V>
+// STAGE: kFull (with or without eigenvectors), or kSpectral (the fused V f(max(Lambda, floor)) V^T of
+// Sec. 4.2-4.4 / App. B.1-B.3, eigenvectors never written).
+template <int N, bool WANT_V, int STAGE>
 __global__ __launch_bounds__(64) void packed_rows_kernel(KernelArgs args) {
+    static_assert(STAGE == kFull || (STAGE == kSpectral && WANT_V), "whole path or fused spectral function");
     using namespace packed;
     using G = Group<16>;
     static_assert(N > 16 && N <= 32, "two rows per lane of a group of 16");
@@ -398,6 +400,38 @@ __global__ __launch_bounds__(64) void packed_rows_kernel(KernelArgs args) {
         info = max(info, (int)__builtin_popcount(bad));
         info |= (int)(min(relaxed, 0x7FFFu) << 16);
     }
+    if (STAGE == kSpectral) {
+        // F = V f(Lambda) V^T straight from V and lambda in LDS: the lane forms w[k] = V[row][k] f(lambda_k)
+        // for its two rows once, then F[row][c] = sum_k w[k] V[c][k] for every c (V[c][k] is one address
+        // per group); F is symmetric, so the entry is stored at F[c][row] and the lanes of a group write
+        // consecutive addresses.
+        float w[R][N];
+        static_for<0, N>([&](auto k_) {
+            constexpr int k = decltype(k_)::value;
+            float lam = sP[k].y * inv_scale;
+            lam = fmaxf(lam, args.fn_floor);
+            const float fl = (args.fn == kFnInvSqrt) ? __builtin_amdgcn_rsqf(lam) : __builtin_amdgcn_sqrtf(lam);
+            static_for<0, R>([&](auto h_) {
+                constexpr int h = decltype(h_)::value;
+                w[h][k] = (k < n) ? sV[k * LD + row[h]] * fl : 0.f;
+            });
+        });
+        float* __restrict__ Fb = args.fn_out + (m0 + grp) * nn;
+        for (int c = 0; c < n; ++c) {
+            float acc[R][2] = {{0.f, 0.f}, {0.f, 0.f}};
+            static_for<0, N>([&](auto k_) {
+                constexpr int k = decltype(k_)::value;
+                const float vc = sV[k * LD + c];
+                static_for<0, R>([&](auto h_) {
+                    constexpr int h = decltype(h_)::value;
+                    acc[h][k & 1] = fmaf(w[h][k], vc, acc[h][k & 1]);
+                });
+            });
+#pragma unroll
+            for (int h = 0; h < R; ++h)
+                if (mine && row[h] < n) Fb[c * n + row[h]] = acc[h][0] + acc[h][1];
+        }
+    }
     float* const sE = sE_all + grp * SW;
     int* const sI = sI_all + grp * SW;
 #pragma unroll
@@ -422,7 +456,7 @@ __global__ __launch_bounds__(64) void packed_rows_kernel(KernelArgs args) {
             Eb[idx] = sE_all[m * SW + (idx - m * n)];
         }
     }
-    if (WANT_V) {
+    if (WANT_V && STAGE == kFull) {
         float* __restrict__ Vb = args.evecs + m0 * nn;
         const float rcp_nn = 1.0f / (float)nn, rcp_n = 1.0f / (float)n;
         chunked_copy<16>(
@@ -442,10 +476,11 @@ __global__ __launch_bounds__(64) void packed_rows_kernel(KernelArgs args) {
 }
 
 template <int N>
-static hipError_t launch_packed_rows_n(const KernelArgs& args, bool want_v, hipStream_t stream) {
+static hipError_t launch_packed_rows_n(const KernelArgs& args, int stage, bool want_v, hipStream_t stream) {
     const unsigned blocks = (unsigned)((args.batch + 3) / 4);
-    if (want_v) return enqueue(packed_rows_kernel<N, true>, dim3(blocks), dim3(64), stream, args);
-    return enqueue(packed_rows_kernel<N, false>, dim3(blocks), dim3(64), stream, args);
+    if (stage == kSpectral) return enqueue(packed_rows_kernel<N, true, kSpectral>, dim3(blocks), dim3(64), stream, args);
+    if (want_v) return enqueue(packed_rows_kernel<N, true, kFull>, dim3(blocks), dim3(64), stream, args);
+    return enqueue(packed_rows_kernel<N, false, kFull>, dim3(blocks), dim3(64), stream, args);
 }
 
 }  // namespace bed

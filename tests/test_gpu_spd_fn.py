@@ -150,13 +150,16 @@ def test_large_batch_small_n():
 @pytest.mark.parametrize("fn", [0, 1])
 def test_where_the_packed_and_lane_kernels_are_dispatched(fn):
     """The fused spectral function at the batch sizes that go to four matrices per wavefront
-    (n <= 16 from batch 2560) and to one matrix per lane (n <= 4 from batch 20480, n <= 8 from batch
+    (n <= 16 from batch 2560, 16 < n <= 32 from batch 4096) and to one matrix per lane (n <= 4 from batch 20480, n <= 8 from batch
     32768), ragged last wavefronts included; 65536 matrices of 4 x 4 are the shape of App. B.3."""
     from paper_2207_04228_amd import binding, workloads
     cases = [("packed_kernel<16>", workloads.config4()),
              ("packed_kernel<12>", workloads.covariance(2560 + 3, 12, 48, 1e-4, 61)),
              ("packed_kernel<8>", workloads.config3(8, batch=4096 + 1)),
              ("packed_kernel<4>", workloads.config2(4096)),
+             ("packed_rows_kernel<32>", workloads.config3(32, batch=4096 + 5)),
+             ("packed_rows_kernel<24>", workloads.covariance(4096 + 2, 21, 84, 1e-4, 65)),
+             ("packed_rows_kernel<20>", workloads.covariance(4096, 17, 68, 1e-4, 66)),
              ("lane_kernel<4>", workloads.config2(65536)),
              ("lane_kernel<4>", workloads.covariance(20480 + 64 + 13, 3, 16, 1e-3, 62)),
              ("lane_kernel<8>", workloads.config3(8, batch=32768 + 7)),
@@ -169,7 +172,7 @@ def test_where_the_packed_and_lane_kernels_are_dispatched(fn):
 def test_floor_and_degenerate_rows_in_the_packed_and_lane_kernels():
     """Zero, diagonal and indefinite matrices inside large batches: the floor acts per matrix."""
     from paper_2207_04228_amd import workloads
-    for batch, n in ((4096, 8), (32768, 8), (20480, 4)):
+    for batch, n in ((4096, 8), (32768, 8), (20480, 4), (4096, 24)):
         A = workloads.covariance(batch, n, 4 * n, 1e-4, 64 + n).copy()
         A[5] = 0.0
         A[6] = np.diag(np.linspace(0.5, 4.0, n)).astype(np.float32)
